@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Throughput of the LASGD update path on one MI355X.
+
+One "step" of this benchmark is one full cycle of the hot path on the
+ResNet-50-shaped workload (K = 8 replicas, 161 tensors, 25,557,032 fp32
+parameters each, global update every m = 4 local steps):
+
+    m-1 x lasgd_local_step   (main stream)
+    1   x lasgd_step_merge   (main stream, waits for the pending mean, re-sends)
+    1   x lasgd_average      (side stream, overlapped with the next local steps)
+
+i.e. m local updates of all K replicas plus one global update.  All inputs are
+synthetic, seeded and already resident in HBM when the timed region starts.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(K: int, N: int, bf16: bool) -> dict:
+    """Bytes each kernel must move per launch (what the method needs, not what caches do)."""
+    # local step: read g, x, v; write x, v (bf16: g and the bf16 copy are 2 bytes each)
+    step = (2 + 4 + 4 + 4 + 4 + 2 if bf16 else 20) * K * N
+    # fused step + global update + re-send: also read s and z (once per parameter), write s
+    step_merge = step + 8 * K * N + 4 * N
+    average = 4 * (K + 1) * N
+    return {"local_step": step, "step_merge": step_merge, "average": average}
+
+
+def cpu_baseline(w, seconds: float = 12.0) -> dict:
+    """The oracle as it stands, timed on this machine's host cores on whole cycles of
+    the same workload (same shapes, K, cadence; one seeded gradient set reused)."""
+    import numpy as np
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd import workloads as W
+    threads = max(1, min(w.K, len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "64"))))
+    nt = len(w.numels)
+    x0 = np.concatenate([W.initial_tensor(w, t) for t in range(nt)])
+    r = np.random.Generator(np.random.Philox(key=12345))
+    g = [(r.standard_normal(w.N, dtype=np.float32) * np.float32(1e-3)) for _ in range(w.K)]
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, [w.weight_decay] * nt, threads=threads)
+    o.set_model(x0)
+    o.prologue(g, w.lr)
+
+    def cycle():
+        for _ in range(w.m):
+            o.iteration(g, w.lr, w.m)
+
+    t0 = time.perf_counter()
+    cycle()
+    first = time.perf_counter() - t0
+    n = int(max(1, min(20, seconds / max(first, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(n):
+        cycle()
+    dt = time.perf_counter() - t0
+    return {"value": w.K * w.N * w.m * n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} full cycles (m={w.m} local steps + global update + mean) of {w.name}, "
+                      f"all K={w.K} replicas and all {w.N} parameters, after one untimed cycle",
+            "ms_per_cycle": 1e3 * dt / n}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="index into the baseline's config list")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true", help="skip the isolated per-kernel and serial legs")
+    ap.add_argument("--tune", type=str, default="", help="k=v,k=v launch-shape knobs (lasgd_tuning fields)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K replicas are resident on it and the All-Reduce is a "
+              "reduction in HBM); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2203_13085_amd import binding as B
+    from paper_2203_13085_amd import workloads as W
+    from paper_2203_13085_amd.driver import DeviceReplicas
+
+    B.load()
+    w = W.config(args.config)
+    bf16 = w.storage == "bf16"
+    tune = {k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(",") if kv)}
+
+    def make(side: bool) -> DeviceReplicas:
+        dev = DeviceReplicas(w, side_stream=side)
+        if tune:
+            dev.ctx.set_tuning(**tune)
+        nt = len(w.numels)
+        x0 = np.concatenate([W.initial_tensor(w, t) for t in range(nt)])
+        if bf16:
+            x0 = W.to_bf16_bits(x0)
+        dev.load_model(x0)
+        # gradients: N(0, 1e-3^2), drawn on the device with a seeded generator (values do not
+        # affect timing; the parity tests use the host-keyed generator instead)
+        gen = torch.Generator(device=dev.dev)
+        gen.manual_seed(w.seed + 1)
+        for k in range(w.K):
+            dev.g[k].copy_((torch.randn(dev.g[k].numel(), generator=gen, device=dev.dev) * 1e-3).to(dev.g[k].dtype))
+        torch.cuda.synchronize()
+        return dev
+
+    def cycle(dev, tau=0):
+        for _ in range(w.m):
+            tau = dev.iteration(w.lr, tau, w.m)
+
+    alg = algorithmic_bytes(w.K, w.N, bf16)
+    cycle_bytes = (w.m - 1) * alg["local_step"] + alg["step_merge"] + alg["average"]
+
+    # ---------------- the timed region: whole cycles, overlapped mean ----------------
+    dev = make(side=True)
+    dev.prologue(w.lr)
+    for _ in range(args.warmup):
+        cycle(dev)
+    dev.ctx.sync()
+    torch.cuda.synchronize()
+    ev = {"local_step": [], "step_merge": [], "average": []}
+
+    def timed_cycle():
+        tau = 0
+        for _ in range(w.m):
+            tau += 1
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            if tau == w.m:
+                a.record(dev.main)
+                dev.ctx.step_merge(w.lr, True)
+                b.record(dev.main)
+                ev["step_merge"].append((a, b))
+                c, d = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                # the mean runs on the side stream once the main stream's work so far is done
+                dev.side.wait_stream(dev.main)
+                c.record(dev.side)
+                dev.ctx.average()
+                d.record(dev.side)
+                ev["average"].append((c, d))
+                tau = 0
+            else:
+                a.record(dev.main)
+                dev.ctx.local_step(w.lr)
+                b.record(dev.main)
+                ev["local_step"].append((a, b))
+
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        timed_cycle()
+    dev.ctx.sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = w.K * w.N * w.m * args.steps / dt
+    kern_ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in ev.items() if v}
+    tuning = dev.ctx.get_tuning()
+
+    detail = {}
+    if not args.no_detail:
+        # ---- each kernel alone (nothing else on the GPU), and the serial (one-stream) cycle ----
+        def alone(fn, n=30):
+            dev.ctx.sync(); torch.cuda.synchronize()
+            ts = []
+            for _ in range(n):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                fn(a, b)
+                dev.ctx.sync(); torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return float(np.median(ts))
+
+        def f_step(a, b):
+            a.record(dev.main); dev.ctx.local_step(w.lr); b.record(dev.main)
+
+        t_step = alone(f_step)
+
+        def f_sm(a, b):
+            # the pending mean is complete before the clock starts
+            dev.ctx.sync()
+            a.record(dev.main); dev.ctx.step_merge(w.lr, True); b.record(dev.main)
+            dev.ctx.sync()
+            dev.ctx.average()
+
+        t_sm = alone(f_sm)
+
+        def f_av(a, b):
+            dev.ctx.merge(True)
+            dev.ctx.sync()
+            a.record(dev.side); dev.ctx.average(); b.record(dev.side)
+
+        t_av = alone(f_av)
+        dev.close()
+        del dev
+        torch.cuda.empty_cache()
+        ser = make(side=False)
+        ser.prologue(w.lr)
+        for _ in range(args.warmup):
+            cycle(ser)
+        ser.ctx.sync(); torch.cuda.synchronize()
+        ns = max(10, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(ns):
+            cycle(ser)
+        ser.ctx.sync(); torch.cuda.synchronize()
+        ms_serial = 1e3 * (time.perf_counter() - t0) / ns
+        ser.close()
+        # time the main stream lost waiting for the mean: what step_merge took in the
+        # pipelined run beyond what it takes alone
+        wait = max(0.0, kern_ms["step_merge"] - t_sm)
+        detail = {
+            "alone_ms": {"local_step": t_step, "step_merge": t_sm, "average": t_av},
+            "alone_GBps": {"local_step": alg["local_step"] / t_step / 1e6, "step_merge": alg["step_merge"] / t_sm / 1e6,
+                           "average": alg["average"] / t_av / 1e6},
+            "ms_per_cycle_one_stream": ms_serial,
+            "overlap": {"T_avg_alone_ms": t_av, "T_wait_ms": wait, "hidden_frac": 1.0 - min(1.0, wait / t_av),
+                        "contention_cost": (ms_per_step - (ms_serial - t_av)) / t_av},
+        }
+    else:
+        dev.close()
+
+    dom = "local_step" if (w.m - 1) * kern_ms.get("local_step", 0.0) >= kern_ms["step_merge"] else "step_merge"
+    achieved = alg[dom] / kern_ms[dom] / 1e6          # bytes / ms -> GB/s
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(w.name, {}).get(dom)
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "params/sec and HBM GB/s (% of peak) for fused LASGD step+merge, K replicas",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, f32 arithmetic" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}]: {w.name}, K={w.K} replicas, {len(w.numels)} tensors, "
+                               f"{w.N} params/replica, merge every m={w.m} local steps, mean on side stream",
+                   "step": "one cycle = m-1 local_step + 1 step_merge(resnapshot) + 1 average",
+                   "K": w.K, "N": w.N, "m": w.m, "lr": w.lr, "momentum": w.momentum, "weight_decay": w.weight_decay,
+                   "nesterov": w.nesterov, "tuning": tuning},
+        "cycle_GBps_algorithmic": cycle_bytes / ms_per_step / 1e6,
+        "cycle_frac_of_peak": cycle_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": kern_ms[dom]},
+        "kernels_in_timed_region": {k: {"avg_ms": v, "GBps": alg[k] / v / 1e6, "frac": alg[k] / v / 1e6 / HBM_PEAK_GBS,
+                                        "launches": len(ev[k])} for k, v in kern_ms.items()},
+    }
+    out.update(detail)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,199 @@
+/*
+ * lasgd.h -- C ABI of the LASGD update library for MI355X (gfx950).
+ *
+ * LASGD (Locally Asynchronous SGD): every worker keeps taking local SGD steps
+ * while an All-Reduce of the models it and its peers "sent" is in flight, and
+ * when the mean z_t arrives replaces its model by z_t plus the progress it
+ * made meanwhile (Algorithm 1, Sec. 4).  This library holds K workers
+ * ("replicas", the paper's P nodes) on ONE GPU and implements the per-iteration
+ * arithmetic of that algorithm; the All-Reduce becomes a reduction over the K
+ * sent models in device memory, run on a second stream.
+ *
+ * Conventions
+ *   - One opaque context owns all K replicas.  Every operation is an
+ *     asynchronous enqueue on a stream borrowed from the caller; nothing
+ *     blocks the host except lasgd_read_state, lasgd_sync and lasgd_destroy.
+ *   - All pointers named "device" are HIP device pointers; all others are
+ *     host pointers.  Config and pointer arrays are copied during the call.
+ *   - Errors are return codes; nothing throws or aborts.  A call that fails
+ *     enqueues no work and leaves the context unchanged.  The text of the
+ *     last failure is available from lasgd_last_error.
+ *   - Calls on one context must come from one host thread at a time.
+ *
+ * Memory owned by the caller:  parameters x[k][t] and gradients g[k][t]
+ *   (one device buffer per replica k and tensor t, numel[t] elements, 16-byte
+ *   aligned, fp32 or bf16 according to `storage`), and both streams.
+ * Memory owned by the library:  momentum v[k], sent models s[k], the mean z,
+ *   the fp32 master copy of the parameters when storage is bf16, and the
+ *   descriptor tables.
+ *
+ * Paper <-> calls.  Prologue (steps 1-5): lasgd_local_step(eta_0),
+ *   lasgd_snapshot, lasgd_average.  Loop iteration without global update
+ *   (steps 6-8): lasgd_local_step(eta).  With global update (steps 6-9):
+ *   lasgd_step_merge(eta, 1) then lasgd_average -- or, unfused,
+ *   lasgd_local_step, lasgd_merge(1), lasgd_average.  The clocks t, t^i and
+ *   tau_i are the caller's; the library only enforces a legal order.
+ */
+#ifndef LASGD_H
+#define LASGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lasgd_ctx lasgd_ctx;
+
+typedef enum {
+    LASGD_OK = 0,
+    LASGD_ERR_INVALID = 1,     /* bad argument: NULL, K < 1, numel < 1, misaligned or
+                                  NULL device pointer, non-finite lr, bad index        */
+    LASGD_ERR_STATE = 2,       /* legal arguments, illegal order (see each call)      */
+    LASGD_ERR_ALLOC = 3,       /* device or host allocation failed                    */
+    LASGD_ERR_HIP = 4,         /* any other HIP runtime failure                       */
+    LASGD_ERR_UNSUPPORTED = 5  /* size beyond what the kernels index (see create)     */
+} lasgd_status;
+
+typedef enum { LASGD_F32 = 0, LASGD_BF16 = 1 } lasgd_dtype;
+
+/* Which array lasgd_read_state copies out. */
+typedef enum {
+    LASGD_STATE_X = 0,   /* local model x^i as fp32 (the master copy when storage is bf16) */
+    LASGD_STATE_V = 1,   /* momentum buffer                                               */
+    LASGD_STATE_S = 2,   /* model last sent to the All-Reduce, x^i_t                      */
+    LASGD_STATE_Z = 3    /* All-Reduce result z_t (replica index ignored)                 */
+} lasgd_state;
+
+typedef struct {
+    int32_t K;                    /* replicas resident on this GPU (the paper's P, Sec. 3); 1..64 */
+    int32_t n_tensors;            /* entries in the parameter list; >= 1                          */
+    const int64_t *numel;         /* host [n_tensors], each >= 1                                  */
+    lasgd_dtype storage;          /* dtype of the caller's parameters and gradients               */
+    float momentum;               /* mu >= 0 (Sec. 5.2: Nesterov momentum); 0 = plain SGD of Alg. 1 */
+    int32_t nesterov;             /* 1: look-ahead form, 0: heavy ball                            */
+    const float *weight_decay;    /* host [n_tensors] L2 coefficients, or NULL => wd_scalar everywhere */
+    float wd_scalar;
+    void *main_stream;            /* hipStream_t for local steps, snapshot, merge (NULL = default stream) */
+    void *side_stream;            /* hipStream_t the mean is computed on; may equal main_stream   */
+} lasgd_config;
+
+/* Launch-shape knobs; results never depend on them.  Zero in any field keeps
+ * the built-in default for that field. */
+typedef struct {
+    int32_t vec;           /* 128-bit vectors per lane per tile: 1, 2 or 4 (tile = 256*vec elements) */
+    int32_t kper_step;     /* replicas one wave handles back to back in local_step (1..K)            */
+    int32_t kper_merge;    /* same for merge / step_merge; K keeps each z tile in registers          */
+    int32_t max_blocks;    /* cap on workgroups per launch (grid-stride beyond it); <0 = no cap      */
+    int32_t avg_split;     /* waves of a workgroup that share one tile's K replicas in average (1,2,4) */
+    int32_t avg_max_blocks;/* cap on workgroups of the average kernel; <0 = no cap                   */
+    int32_t nontemporal;   /* bit 0: streaming loads, bit 1: streaming stores                        */
+} lasgd_tuning;
+
+/*
+ * Create a context for K replicas of a parameter list and allocate the
+ * library-owned state (v = 0, s, z, master copy), on the current device.
+ * Errors: INVALID (NULL, K outside 1..64, n_tensors < 1, numel < 1, negative or
+ * non-finite momentum / weight decay, unknown storage), UNSUPPORTED (a padded
+ * replica larger than 2^31 - 2^20 elements), ALLOC, HIP.  *out is NULL on failure.
+ */
+lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out);
+
+/*
+ * Attach replica k's buffers: params[t] and grads[t] are device pointers to
+ * numel[t] elements of the storage dtype, 16-byte aligned; the host arrays
+ * [n_tensors] are copied, the device buffers stay the caller's and must
+ * outlive their use.  May be called again to re-point a replica (e.g. at a
+ * rotating gradient buffer); waits for work already enqueued.
+ * Errors: INVALID (NULL, k out of range, NULL or misaligned entry), HIP.
+ */
+lasgd_status lasgd_bind(lasgd_ctx *ctx, int32_t k, void *const *params, void *const *grads);
+
+/*
+ * bf16 storage only: master <- exact widening of the bound parameters,
+ * v <- 0 (Algorithm 1 step 1).  Required once before the first step.
+ * Errors: STATE (storage is fp32; a replica is unbound), HIP.
+ */
+lasgd_status lasgd_init_master(lasgd_ctx *ctx);
+
+/*
+ * Local update of all K replicas (Algorithm 1 steps 3 and 7, with the optimizer
+ * of Sec. 5.2):  g' = g + wd*x;  v = mu*v + g';  d = g' + mu*v (Nesterov) or v;
+ * x = x - lr*d.  Reads g, x, v; writes x, v (bf16 storage: acts on the master
+ * and also rewrites the bf16 parameters).  Main stream.
+ * Errors: INVALID (non-finite lr), STATE (a replica is unbound; bf16 master not
+ * initialised), HIP.
+ */
+lasgd_status lasgd_local_step(lasgd_ctx *ctx, float lr);
+
+/*
+ * "Send x^i to All-Reduce" (Algorithm 1 steps 4 and 9c): s[k] <- x[k].  Main stream.
+ * Errors: STATE (an average is in flight and not yet merged: the side stream
+ * may still be reading s), HIP.
+ */
+lasgd_status lasgd_snapshot(lasgd_ctx *ctx);
+
+/*
+ * The All-Reduce itself (Sec. 3, Eq. 8): z = (1/K) sum_k s[k], accumulated in
+ * fp64 and rounded once.  Runs on the side stream after everything enqueued so
+ * far on the main stream; the main stream does not wait for it.
+ * Errors: STATE (no snapshot since the last merge that did not re-snapshot;
+ * a previous average is still unmerged), HIP.
+ */
+lasgd_status lasgd_average(lasgd_ctx *ctx);
+
+/*
+ * "All Reduce done?" (Algorithm 1 step 9): *done = 1 if the last average has
+ * finished on the device, else 0.  Never blocks.
+ * Errors: INVALID (NULL), STATE (no average launched), HIP.
+ */
+lasgd_status lasgd_average_done(lasgd_ctx *ctx, int32_t *done);
+
+/*
+ * Global update (Algorithm 1 step 9a-b): x[k] <- z + (x[k] - s[k]); with
+ * resnapshot != 0 also s[k] <- x[k] (step 9c).  The main stream first waits for
+ * the pending average.
+ * Errors: STATE (no average launched since the last merge), HIP.
+ */
+lasgd_status lasgd_merge(lasgd_ctx *ctx, int32_t resnapshot);
+
+/*
+ * Steps 7 and 9a-c of one loop iteration in a single pass over memory:
+ * exactly lasgd_local_step(lr) followed by lasgd_merge(resnapshot), with the
+ * same roundings.
+ * Errors: as lasgd_local_step and lasgd_merge.
+ */
+lasgd_status lasgd_step_merge(lasgd_ctx *ctx, float lr, int32_t resnapshot);
+
+/*
+ * Parity probe: wait for both streams, then copy one array to host memory as
+ * fp32.  tensor >= 0: that tensor of replica k, n must equal numel[tensor];
+ * tensor == -1: all tensors of replica k back to back (no padding), n must
+ * equal the sum of numel.  k is ignored for LASGD_STATE_Z.
+ * Errors: INVALID (NULL, bad which / k / tensor / n), STATE (X of an unbound
+ * replica), HIP.
+ */
+lasgd_status lasgd_read_state(lasgd_ctx *ctx, int32_t which, int32_t k, int32_t tensor,
+                              float *host_dst, int64_t n);
+
+/* Wait until both streams have finished everything this context enqueued. */
+lasgd_status lasgd_sync(lasgd_ctx *ctx);
+
+/* Change launch-shape knobs (waits for enqueued work first).
+ * Errors: INVALID (NULL, a field outside its documented values), HIP, ALLOC. */
+lasgd_status lasgd_set_tuning(lasgd_ctx *ctx, const lasgd_tuning *t);
+
+/* The knobs currently in effect. */
+lasgd_status lasgd_get_tuning(const lasgd_ctx *ctx, lasgd_tuning *out);
+
+/* Text of the last failure on this context ("" if none); owned by the context.
+ * With ctx == NULL: text of the last lasgd_create failure on this thread. */
+const char *lasgd_last_error(const lasgd_ctx *ctx);
+
+/* Wait for enqueued work, free library-owned memory.  NULL is allowed. */
+void lasgd_destroy(lasgd_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASGD_H */

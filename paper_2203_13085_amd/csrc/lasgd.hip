@@ -1,0 +1,550 @@
+// Host side of the LASGD update library: context, validation, state machine,
+// descriptor tables, launches.  The C ABI is declared in include/lasgd.h.
+//
+// Stream protocol (single-GPU image of "the All-Reduce runs while the node
+// keeps computing", Sec. 4):
+//   main stream:  local_step ... snapshot/merge --evA--> ...        wait evZ, merge
+//   side stream:                          wait evA, average --evZ-->
+// evA orders the side stream's reads of s after the main stream's writes;
+// evZ orders the main stream's reads of z after the side stream's writes.
+// The state machine refuses call orders in which s or z could be overwritten
+// while the other stream may still read them.
+#include "lasgd_kernels.hip.h"
+#include "../../include/lasgd.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace lasgd;
+
+namespace {
+
+constexpr int kMaxK = 64;
+constexpr uint64_t kArenaAlign = 64;                       // elements: every tensor starts on 256 B
+constexpr uint64_t kMaxNpad = (1ull << 31) - (1ull << 20); // tile offsets stay far inside 32-bit element counts
+
+thread_local std::string g_create_error;
+
+} // namespace
+
+struct lasgd_ctx {
+    int32_t K = 0, n_tensors = 0;
+    lasgd_dtype storage = LASGD_F32;
+    float mu = 0.f, wd_scalar = 0.f;
+    int32_t nesterov = 0;
+    std::vector<int64_t> numel;
+    std::vector<float> wd;
+    std::vector<uint64_t> aoff;      // arena offset of each tensor (elements)
+    uint64_t npad = 0, ntotal = 0;
+    hipStream_t main = nullptr, side = nullptr;
+    hipEvent_t evA = nullptr, evZ = nullptr;
+    int device = 0;
+
+    // device memory (one allocation, carved up)
+    char *arena = nullptr;
+    float *v = nullptr, *s = nullptr, *z = nullptr, *x32 = nullptr;
+    Tile *tiles = nullptr;
+    uint32_t ntiles = 0;
+    void **xptr = nullptr, **gptr = nullptr;     // device tables [K*n_tensors]
+    std::vector<void *> h_xptr, h_gptr;
+    std::vector<char> bound;
+    int32_t n_bound = 0;
+
+    // protocol state
+    bool master_ready = false;   // bf16: master copy initialised
+    bool snap_valid = false;     // s holds the models to be averaged next
+    bool avg_pending = false;    // an average was launched and not yet merged
+    bool avg_ever = false;
+
+    lasgd_tuning tune{};
+    std::string err;
+};
+
+namespace {
+
+lasgd_status fail(lasgd_ctx *ctx, lasgd_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    else g_create_error = buf;
+    return st;
+}
+
+#define LASGD_HIP(ctx, call)                                                                   \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? LASGD_ERR_ALLOC : LASGD_ERR_HIP,      \
+                        "%s failed: %s", #call, hipGetErrorString(e_));                        \
+    } while (0)
+
+uint64_t round_up(uint64_t a, uint64_t b) { return (a + b - 1) / b * b; }
+
+bool is_pow2(uint32_t k) { return k && !(k & (k - 1)); }
+
+// Build (on the host) the tile list for 256*vec-element tiles.
+std::vector<Tile> build_tiles(const lasgd_ctx &c, int vec)
+{
+    std::vector<Tile> t;
+    const uint64_t T = 256ull * vec;
+    for (int32_t i = 0; i < c.n_tensors; ++i) {
+        const uint64_t n = (uint64_t)c.numel[i];
+        for (uint64_t o = 0; o < n; o += T) {
+            Tile d{};
+            d.toff = o;
+            d.aoff = c.aoff[i] + o;
+            d.tensor = (uint32_t)i;
+            d.count = (uint32_t)((n - o < T) ? n - o : T);
+            d.wd = c.wd[i];
+            t.push_back(d);
+        }
+    }
+    return t;
+}
+
+lasgd_status upload_tiles(lasgd_ctx *c, int vec)
+{
+    std::vector<Tile> t = build_tiles(*c, vec);
+    if (t.size() > 0x7fffffffull / kMaxK) return fail(c, LASGD_ERR_UNSUPPORTED, "too many tiles (%zu)", t.size());
+    Tile *d = nullptr;
+    LASGD_HIP(c, hipMalloc(&d, t.size() * sizeof(Tile)));
+    hipError_t e = hipMemcpy(d, t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(d);
+        return fail(c, LASGD_ERR_HIP, "tile table upload failed: %s", hipGetErrorString(e));
+    }
+    if (c->tiles) (void)hipFree(c->tiles);
+    c->tiles = d;
+    c->ntiles = (uint32_t)t.size();
+    return LASGD_OK;
+}
+
+lasgd_tuning default_tuning(const lasgd_ctx &c)
+{
+    lasgd_tuning t{};
+    t.vec = 2;
+    t.kper_step = 1;
+    t.kper_merge = c.K;
+    t.max_blocks = -1;
+    t.avg_split = 1;
+    t.avg_max_blocks = -1;
+    t.nontemporal = 0;
+    return t;
+}
+
+template <int VEC, int OP, bool BF16>
+hipError_t launch_nt(const ApplyArgs &a, dim3 grid, hipStream_t st, int nt)
+{
+    switch (nt & 3) {
+    case 0: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 0>), grid, dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 1>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 2>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 3>), grid, dim3(256), 0, st, a); break;
+    }
+    return hipGetLastError();
+}
+
+template <int OP, bool BF16>
+hipError_t launch_vec(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt)
+{
+    switch (vec) {
+    case 1: return launch_nt<1, OP, BF16>(a, grid, st, nt);
+    case 2: return launch_nt<2, OP, BF16>(a, grid, st, nt);
+    default: return launch_nt<4, OP, BF16>(a, grid, st, nt);
+    }
+}
+
+template <int OP>
+hipError_t launch_op(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt, bool bf16)
+{
+    return bf16 ? launch_vec<OP, true>(a, grid, st, vec, nt) : launch_vec<OP, false>(a, grid, st, vec, nt);
+}
+
+// Enqueue one multi-tensor pass on the main stream.
+lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
+{
+    ApplyArgs a{};
+    a.tiles = c->tiles;
+    a.xptr = c->xptr;
+    a.gptr = c->gptr;
+    a.x32 = c->x32;
+    a.v = c->v;
+    a.s = c->s;
+    a.z = c->z;
+    a.npad = c->npad;
+    a.ntiles = c->ntiles;
+    a.K = (uint32_t)c->K;
+    a.n_tensors = (uint32_t)c->n_tensors;
+    int kper = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.kper_merge : c->tune.kper_step;
+    if (kper < 1) kper = 1;
+    if (kper > c->K) kper = c->K;
+    a.kper = (uint32_t)kper;
+    a.kgroups = (uint32_t)((c->K + kper - 1) / kper);
+    const uint64_t nitems = (uint64_t)a.ntiles * a.kgroups;
+    if (nitems == 0 || nitems > 0x7fffffffull) return fail(c, LASGD_ERR_UNSUPPORTED, "work-item count %llu out of range", (unsigned long long)nitems);
+    a.nitems = (uint32_t)nitems;
+    a.neg_lr = -lr;
+    a.mu = c->mu;
+    a.nesterov = c->nesterov;
+    a.resnap = resnap;
+    uint64_t blocks = (nitems + 3) / 4;                     // four waves per workgroup
+    if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
+    const dim3 grid((uint32_t)blocks);
+    const bool bf16 = c->storage == LASGD_BF16;
+    hipError_t e = hipSuccess;
+    switch (op) {
+    case OP_STEP: e = launch_op<OP_STEP>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
+    case OP_MERGE: e = launch_op<OP_MERGE>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
+    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
+    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
+    case OP_INIT: e = launch_vec<OP_INIT, true>(a, grid, c->main, c->tune.vec, c->tune.nontemporal); break;
+    default: return fail(c, LASGD_ERR_INVALID, "unknown op %d", op);
+    }
+    if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return LASGD_OK;
+}
+
+lasgd_status enqueue_average(lasgd_ctx *c)
+{
+    AvgArgs a{};
+    a.s = c->s;
+    a.z = c->z;
+    a.npad = c->npad;
+    a.nvec = c->npad / 4;
+    a.K = (uint32_t)c->K;
+    a.use_mul = is_pow2((uint32_t)c->K) ? 1 : 0;
+    a.inv_k = 1.0 / (double)c->K;
+    a.k_as_double = (double)c->K;
+    const int split = c->tune.avg_split;
+    const uint64_t cols = 256u / (uint32_t)split;
+    uint64_t blocks = (a.nvec + cols - 1) / cols;
+    if (c->tune.avg_max_blocks > 0 && blocks > (uint64_t)c->tune.avg_max_blocks) blocks = (uint64_t)c->tune.avg_max_blocks;
+    if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
+    const dim3 grid((uint32_t)blocks);
+    const bool nt = (c->tune.nontemporal & 1) != 0;
+    if (split == 1) {
+        if (nt) hipLaunchKernelGGL((average_kernel<3>), grid, dim3(256), 0, c->side, a);
+        else hipLaunchKernelGGL((average_kernel<0>), grid, dim3(256), 0, c->side, a);
+    } else if (split == 2) {
+        if (nt) hipLaunchKernelGGL((average_split_kernel<2, 3>), grid, dim3(256), 0, c->side, a);
+        else hipLaunchKernelGGL((average_split_kernel<2, 0>), grid, dim3(256), 0, c->side, a);
+    } else {
+        if (nt) hipLaunchKernelGGL((average_split_kernel<4, 3>), grid, dim3(256), 0, c->side, a);
+        else hipLaunchKernelGGL((average_split_kernel<4, 0>), grid, dim3(256), 0, c->side, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "average launch failed: %s", hipGetErrorString(e));
+    return LASGD_OK;
+}
+
+lasgd_status check_ready_to_step(lasgd_ctx *c, float lr)
+{
+    if (!std::isfinite(lr)) return fail(c, LASGD_ERR_INVALID, "learning rate is not finite");
+    if (c->n_bound != c->K) return fail(c, LASGD_ERR_STATE, "%d of %d replicas are bound", c->n_bound, c->K);
+    if (c->storage == LASGD_BF16 && !c->master_ready)
+        return fail(c, LASGD_ERR_STATE, "bf16 storage: call lasgd_init_master first");
+    return LASGD_OK;
+}
+
+void release(lasgd_ctx *c)
+{
+    if (c->arena) (void)hipFree(c->arena);
+    if (c->tiles) (void)hipFree(c->tiles);
+    if (c->xptr) (void)hipFree(c->xptr);
+    if (c->evA) (void)hipEventDestroy(c->evA);
+    if (c->evZ) (void)hipEventDestroy(c->evZ);
+    delete c;
+}
+
+} // namespace
+
+extern "C" {
+
+lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return fail(nullptr, LASGD_ERR_INVALID, "NULL argument");
+    if (cfg->K < 1 || cfg->K > kMaxK) return fail(nullptr, LASGD_ERR_INVALID, "K = %d outside 1..%d", cfg->K, kMaxK);
+    if (cfg->n_tensors < 1 || !cfg->numel) return fail(nullptr, LASGD_ERR_INVALID, "empty parameter list");
+    if (cfg->storage != LASGD_F32 && cfg->storage != LASGD_BF16) return fail(nullptr, LASGD_ERR_INVALID, "unknown storage dtype");
+    if (!std::isfinite(cfg->momentum) || cfg->momentum < 0.f) return fail(nullptr, LASGD_ERR_INVALID, "momentum must be finite and >= 0");
+    if (!std::isfinite(cfg->wd_scalar) || cfg->wd_scalar < 0.f) return fail(nullptr, LASGD_ERR_INVALID, "weight decay must be finite and >= 0");
+    lasgd_ctx *c = new (std::nothrow) lasgd_ctx;
+    if (!c) return fail(nullptr, LASGD_ERR_ALLOC, "out of host memory");
+    c->K = cfg->K;
+    c->n_tensors = cfg->n_tensors;
+    c->storage = cfg->storage;
+    c->mu = cfg->momentum;
+    c->nesterov = cfg->nesterov ? 1 : 0;
+    c->wd_scalar = cfg->wd_scalar;
+    c->main = (hipStream_t)cfg->main_stream;
+    c->side = (hipStream_t)cfg->side_stream;
+    uint64_t off = 0, total = 0;
+    for (int32_t i = 0; i < cfg->n_tensors; ++i) {
+        if (cfg->numel[i] < 1) { delete c; return fail(nullptr, LASGD_ERR_INVALID, "numel[%d] = %lld", i, (long long)cfg->numel[i]); }
+        const float w = cfg->weight_decay ? cfg->weight_decay[i] : cfg->wd_scalar;
+        if (!std::isfinite(w) || w < 0.f) { delete c; return fail(nullptr, LASGD_ERR_INVALID, "weight_decay[%d] must be finite and >= 0", i); }
+        c->numel.push_back(cfg->numel[i]);
+        c->wd.push_back(w);
+        c->aoff.push_back(off);
+        total += (uint64_t)cfg->numel[i];
+        off += round_up((uint64_t)cfg->numel[i], kArenaAlign);
+        if (off > kMaxNpad) { delete c; return fail(nullptr, LASGD_ERR_UNSUPPORTED, "more than %llu elements per replica", (unsigned long long)kMaxNpad); }
+    }
+    c->npad = off;
+    c->ntotal = total;
+    c->bound.assign((size_t)c->K, 0);
+    c->h_xptr.assign((size_t)c->K * c->n_tensors, nullptr);
+    c->h_gptr.assign((size_t)c->K * c->n_tensors, nullptr);
+    c->tune = default_tuning(*c);
+
+#define CREATE_HIP(call)                                                                       \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            lasgd_status st_ = fail(nullptr, e_ == hipErrorOutOfMemory ? LASGD_ERR_ALLOC : LASGD_ERR_HIP, \
+                                    "%s failed: %s", #call, hipGetErrorString(e_));            \
+            release(c);                                                                        \
+            return st_;                                                                        \
+        }                                                                                      \
+    } while (0)
+
+    CREATE_HIP(hipGetDevice(&c->device));
+    const bool bf16 = c->storage == LASGD_BF16;
+    const uint64_t per = c->npad * sizeof(float);
+    const uint64_t n_arrays = (uint64_t)c->K * (bf16 ? 3 : 2) + 1;       // v, s (, x32), z
+    CREATE_HIP(hipMalloc((void **)&c->arena, n_arrays * per));
+    CREATE_HIP(hipMemsetAsync(c->arena, 0, n_arrays * per, c->main));
+    c->v = (float *)c->arena;
+    c->s = c->v + (uint64_t)c->K * c->npad;
+    c->z = c->s + (uint64_t)c->K * c->npad;
+    c->x32 = bf16 ? c->z + c->npad : nullptr;
+    const size_t tab = (size_t)c->K * c->n_tensors * sizeof(void *);
+    CREATE_HIP(hipMalloc((void **)&c->xptr, 2 * tab));
+    c->gptr = c->xptr + (size_t)c->K * c->n_tensors;
+    CREATE_HIP(hipMemset(c->xptr, 0, 2 * tab));
+    CREATE_HIP(hipEventCreateWithFlags(&c->evA, hipEventDisableTiming));
+    CREATE_HIP(hipEventCreateWithFlags(&c->evZ, hipEventDisableTiming));
+    lasgd_status st = upload_tiles(c, c->tune.vec);
+    if (st != LASGD_OK) {
+        g_create_error = c->err;
+        release(c);
+        return st;
+    }
+    CREATE_HIP(hipStreamSynchronize(c->main));
+#undef CREATE_HIP
+    *out = c;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_bind(lasgd_ctx *c, int32_t k, void *const *params, void *const *grads)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!params || !grads) return fail(c, LASGD_ERR_INVALID, "NULL pointer array");
+    if (k < 0 || k >= c->K) return fail(c, LASGD_ERR_INVALID, "replica %d outside 0..%d", k, c->K - 1);
+    for (int32_t t = 0; t < c->n_tensors; ++t) {
+        if (!params[t] || !grads[t]) return fail(c, LASGD_ERR_INVALID, "NULL buffer for tensor %d", t);
+        if (((uintptr_t)params[t] | (uintptr_t)grads[t]) & 15u)
+            return fail(c, LASGD_ERR_INVALID, "buffer of tensor %d is not 16-byte aligned", t);
+    }
+    LASGD_HIP(c, hipStreamSynchronize(c->main));
+    const size_t base = (size_t)k * c->n_tensors, bytes = (size_t)c->n_tensors * sizeof(void *);
+    LASGD_HIP(c, hipMemcpy(c->xptr + base, params, bytes, hipMemcpyHostToDevice));
+    LASGD_HIP(c, hipMemcpy(c->gptr + base, grads, bytes, hipMemcpyHostToDevice));
+    memcpy(&c->h_xptr[base], params, bytes);
+    memcpy(&c->h_gptr[base], grads, bytes);
+    if (!c->bound[(size_t)k]) {
+        c->bound[(size_t)k] = 1;
+        ++c->n_bound;
+    }
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_init_master(lasgd_ctx *c)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (c->storage != LASGD_BF16) return fail(c, LASGD_ERR_STATE, "storage is fp32: there is no master copy");
+    if (c->n_bound != c->K) return fail(c, LASGD_ERR_STATE, "%d of %d replicas are bound", c->n_bound, c->K);
+    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "an average is in flight");
+    lasgd_status st = enqueue_apply(c, OP_INIT, 0.f, 0);
+    if (st != LASGD_OK) return st;
+    c->master_ready = true;
+    c->snap_valid = false;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_local_step(lasgd_ctx *c, float lr)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    lasgd_status st = check_ready_to_step(c, lr);
+    if (st != LASGD_OK) return st;
+    return enqueue_apply(c, OP_STEP, lr, 0);
+}
+
+lasgd_status lasgd_snapshot(lasgd_ctx *c)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    lasgd_status st = check_ready_to_step(c, 0.f);
+    if (st != LASGD_OK) return st;
+    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "an average is in flight and not merged: s may still be read");
+    st = enqueue_apply(c, OP_SNAPSHOT, 0.f, 0);
+    if (st != LASGD_OK) return st;
+    c->snap_valid = true;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_average(lasgd_ctx *c)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "the previous average has not been merged");
+    if (!c->snap_valid) return fail(c, LASGD_ERR_STATE, "no snapshot to average");
+    if (c->side != c->main) {
+        LASGD_HIP(c, hipEventRecord(c->evA, c->main));
+        LASGD_HIP(c, hipStreamWaitEvent(c->side, c->evA, 0));
+    }
+    lasgd_status st = enqueue_average(c);
+    if (st != LASGD_OK) return st;
+    LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
+    c->avg_pending = true;
+    c->avg_ever = true;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_average_done(lasgd_ctx *c, int32_t *done)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!done) return fail(c, LASGD_ERR_INVALID, "NULL argument");
+    if (!c->avg_ever) return fail(c, LASGD_ERR_STATE, "no average has been launched");
+    hipError_t e = hipEventQuery(c->evZ);
+    if (e == hipSuccess) *done = 1;
+    else if (e == hipErrorNotReady) *done = 0;
+    else return fail(c, LASGD_ERR_HIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+    return LASGD_OK;
+}
+
+static lasgd_status merge_common(lasgd_ctx *c, int op, float lr, int32_t resnapshot)
+{
+    lasgd_status st = check_ready_to_step(c, lr);
+    if (st != LASGD_OK) return st;
+    if (!c->avg_pending) return fail(c, LASGD_ERR_STATE, "no average launched since the last merge");
+    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    st = enqueue_apply(c, op, lr, resnapshot ? 1 : 0);
+    if (st != LASGD_OK) return st;
+    c->avg_pending = false;
+    c->snap_valid = resnapshot != 0;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_merge(lasgd_ctx *c, int32_t resnapshot)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    return merge_common(c, OP_MERGE, 0.f, resnapshot);
+}
+
+lasgd_status lasgd_step_merge(lasgd_ctx *c, float lr, int32_t resnapshot)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    return merge_common(c, OP_STEP_MERGE, lr, resnapshot);
+}
+
+lasgd_status lasgd_sync(lasgd_ctx *c)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    LASGD_HIP(c, hipStreamSynchronize(c->main));
+    if (c->side != c->main) LASGD_HIP(c, hipStreamSynchronize(c->side));
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_read_state(lasgd_ctx *c, int32_t which, int32_t k, int32_t tensor, float *dst, int64_t n)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!dst) return fail(c, LASGD_ERR_INVALID, "NULL destination");
+    if (which < LASGD_STATE_X || which > LASGD_STATE_Z) return fail(c, LASGD_ERR_INVALID, "unknown state array %d", which);
+    if (which == LASGD_STATE_Z) k = 0;
+    if (k < 0 || k >= c->K) return fail(c, LASGD_ERR_INVALID, "replica %d outside 0..%d", k, c->K - 1);
+    if (tensor < -1 || tensor >= c->n_tensors) return fail(c, LASGD_ERR_INVALID, "tensor %d outside -1..%d", tensor, c->n_tensors - 1);
+    const int64_t want = tensor < 0 ? (int64_t)c->ntotal : c->numel[(size_t)tensor];
+    if (n != want) return fail(c, LASGD_ERR_INVALID, "n = %lld, expected %lld", (long long)n, (long long)want);
+    const bool user_x = which == LASGD_STATE_X && c->storage == LASGD_F32;
+    if (user_x && !c->bound[(size_t)k]) return fail(c, LASGD_ERR_STATE, "replica %d is not bound", k);
+    lasgd_status st = lasgd_sync(c);
+    if (st != LASGD_OK) return st;
+    const float *base = which == LASGD_STATE_V ? c->v : which == LASGD_STATE_S ? c->s : which == LASGD_STATE_Z ? c->z : c->x32;
+    const int32_t t0 = tensor < 0 ? 0 : tensor, t1 = tensor < 0 ? c->n_tensors : tensor + 1;
+    float *out = dst;
+    for (int32_t t = t0; t < t1; ++t) {
+        const void *src = user_x ? c->h_xptr[(size_t)k * c->n_tensors + t]
+                                 : (const void *)(base + (which == LASGD_STATE_Z ? 0 : (uint64_t)k * c->npad) + c->aoff[(size_t)t]);
+        LASGD_HIP(c, hipMemcpy(out, src, (size_t)c->numel[(size_t)t] * sizeof(float), hipMemcpyDeviceToHost));
+        out += c->numel[(size_t)t];
+    }
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!t) return fail(c, LASGD_ERR_INVALID, "NULL argument");
+    lasgd_tuning n = c->tune;
+    if (t->vec) {
+        if (t->vec != 1 && t->vec != 2 && t->vec != 4) return fail(c, LASGD_ERR_INVALID, "vec must be 1, 2 or 4");
+        n.vec = t->vec;
+    }
+    if (t->kper_step) {
+        if (t->kper_step < 1 || t->kper_step > c->K) return fail(c, LASGD_ERR_INVALID, "kper_step outside 1..K");
+        n.kper_step = t->kper_step;
+    }
+    if (t->kper_merge) {
+        if (t->kper_merge < 1 || t->kper_merge > c->K) return fail(c, LASGD_ERR_INVALID, "kper_merge outside 1..K");
+        n.kper_merge = t->kper_merge;
+    }
+    if (t->max_blocks) n.max_blocks = t->max_blocks;
+    if (t->avg_split) {
+        if (t->avg_split != 1 && t->avg_split != 2 && t->avg_split != 4) return fail(c, LASGD_ERR_INVALID, "avg_split must be 1, 2 or 4");
+        n.avg_split = t->avg_split;
+    }
+    if (t->avg_max_blocks) n.avg_max_blocks = t->avg_max_blocks;
+    if (t->nontemporal) {
+        if (t->nontemporal < 0 || t->nontemporal > 4) return fail(c, LASGD_ERR_INVALID, "nontemporal outside 0..4");
+        n.nontemporal = t->nontemporal == 4 ? 0 : t->nontemporal;      // 4 = switch the hints off again
+    }
+    lasgd_status st = lasgd_sync(c);
+    if (st != LASGD_OK) return st;
+    if (n.vec != c->tune.vec) {
+        st = upload_tiles(c, n.vec);
+        if (st != LASGD_OK) return st;
+    }
+    c->tune = n;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_get_tuning(const lasgd_ctx *c, lasgd_tuning *out)
+{
+    if (!c || !out) return LASGD_ERR_INVALID;
+    *out = c->tune;
+    return LASGD_OK;
+}
+
+const char *lasgd_last_error(const lasgd_ctx *c)
+{
+    return c ? c->err.c_str() : g_create_error.c_str();
+}
+
+void lasgd_destroy(lasgd_ctx *c)
+{
+    if (!c) return;
+    (void)hipStreamSynchronize(c->main);
+    if (c->side != c->main) (void)hipStreamSynchronize(c->side);
+    release(c);
+}
+
+} // extern "C"

@@ -1,0 +1,390 @@
+// Device code of the LASGD update library (gfx950 / CDNA4, wave64).
+//
+// Everything here is bandwidth-bound streaming: a handful of fp32 FMAs per
+// 20-28 bytes moved, so there is no matrix-core work.  What matters is that
+// every lane moves 128 bits per access, that a wave covers a contiguous
+// kilobyte per instruction, that many independent loads are in flight before
+// the first use, and that the mean z (shared by all K replicas) is fetched
+// once per tile and kept in registers while the wave walks the replicas.
+//
+// Arithmetic is pinned: contraction is off for this file, so only the
+// __builtin_fmaf calls below fuse.  Local update: Algorithm 1 steps 3 and 7
+// with the optimizer of Sec. 5.2; global update: step 9a-b; mean: Sec. 3 Eq. 8.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lasgd {
+
+// One tile = up to 256*VEC consecutive elements of ONE tensor, handled by one
+// wave: lane l owns elements [4l, 4l+4) of each 256-element row of the tile.
+struct Tile {
+    uint64_t toff;     // first element, relative to the tensor's start
+    uint64_t aoff;     // first element, relative to a replica's start in the library arenas
+    uint32_t tensor;   // index into the pointer tables
+    uint32_t count;    // elements in this tile (<= 256*VEC; smaller only at a tensor's end)
+    float wd;          // the tensor's weight decay
+    uint32_t pad_;
+};
+static_assert(sizeof(Tile) == 32, "tile descriptors are read as two 16-byte scalar loads");
+
+enum Op : int { OP_STEP = 0, OP_MERGE = 1, OP_STEP_MERGE = 2, OP_SNAPSHOT = 3, OP_INIT = 4 };
+
+struct ApplyArgs {
+    const Tile *tiles;
+    void *const *xptr;      // [K * n_tensors] caller's parameters (fp32 or bf16)
+    void *const *gptr;      // [K * n_tensors] caller's gradients  (fp32 or bf16)
+    float *x32;             // bf16 storage only: fp32 master, [K][npad]
+    float *v;               // momentum,     [K][npad]
+    float *s;               // sent models,  [K][npad]
+    const float *z;         // mean,         [npad]
+    uint64_t npad;          // elements per replica in the arenas
+    uint32_t ntiles, K, n_tensors;
+    uint32_t kper;          // replicas a wave handles back to back
+    uint32_t kgroups;       // ceil(K / kper)
+    uint32_t nitems;        // ntiles * kgroups
+    float neg_lr, mu;
+    int32_t nesterov, resnap;
+};
+
+// ---- 128-bit / 64-bit accesses, optionally with the streaming hint --------
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+template <int NT> __device__ __forceinline__ float4 ld4(const float *p)
+{
+    if constexpr (NT & 1) {
+        f32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+        return make_float4(r.x, r.y, r.z, r.w);
+    } else {
+        return *reinterpret_cast<const float4 *>(p);
+    }
+}
+template <int NT> __device__ __forceinline__ void st4(float *p, float4 a)
+{
+    if constexpr (NT & 2) {
+        f32x4_t r = {a.x, a.y, a.z, a.w};
+        __builtin_nontemporal_store(r, reinterpret_cast<f32x4_t *>(p));
+    } else {
+        *reinterpret_cast<float4 *>(p) = a;
+    }
+}
+template <int NT> __device__ __forceinline__ uint2 ld2(const uint16_t *p)
+{
+    if constexpr (NT & 1) {
+        u32x2_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(p));
+        return make_uint2(r.x, r.y);
+    } else {
+        return *reinterpret_cast<const uint2 *>(p);
+    }
+}
+template <int NT> __device__ __forceinline__ void st2(uint16_t *p, uint2 a)
+{
+    if constexpr (NT & 2) {
+        u32x2_t r = {a.x, a.y};
+        __builtin_nontemporal_store(r, reinterpret_cast<u32x2_t *>(p));
+    } else {
+        *reinterpret_cast<uint2 *>(p) = a;
+    }
+}
+
+// ---- bf16 <-> fp32 ----------------------------------------------------------
+__device__ __forceinline__ float bf16_widen(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Round to nearest, ties to even, by adding 0x7fff plus the kept LSB and
+// truncating; NaN is kept a quiet NaN.
+__device__ __forceinline__ uint32_t bf16_round(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = (u >> 16) | 0x40u;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? nan : r;
+}
+__device__ __forceinline__ float4 widen4(uint2 p)
+{
+    return make_float4(bf16_widen(p.x & 0xffffu), bf16_widen(p.x >> 16),
+                       bf16_widen(p.y & 0xffffu), bf16_widen(p.y >> 16));
+}
+__device__ __forceinline__ uint2 round4(float4 a)
+{
+    return make_uint2(bf16_round(a.x) | (bf16_round(a.y) << 16),
+                      bf16_round(a.z) | (bf16_round(a.w) << 16));
+}
+
+// ---- the arithmetic, one element -------------------------------------------
+// Local update (Algorithm 1 step 7; Sec. 5.2): four fused multiply-adds.
+__device__ __forceinline__ void step_elem(float &x, float &v, float g, float wd, float mu,
+                                          float neg_lr, int nesterov)
+{
+    float g1 = __builtin_fmaf(wd, x, g);
+    float vn = __builtin_fmaf(mu, v, g1);
+    float d = nesterov ? __builtin_fmaf(mu, vn, g1) : vn;
+    x = __builtin_fmaf(neg_lr, d, x);
+    v = vn;
+}
+// Global update (step 9a): z + (x - s), parenthesised as printed.
+__device__ __forceinline__ float merge_elem(float x, float s, float z)
+{
+    float progress = x - s;
+    return z + progress;
+}
+
+#define LASGD_FOR4(body)                                                                       \
+    {                                                                                          \
+        { constexpr int c = 0; body }                                                          \
+        { constexpr int c = 1; body }                                                          \
+        { constexpr int c = 2; body }                                                          \
+        { constexpr int c = 3; body }                                                          \
+    }
+__device__ __forceinline__ float &comp(float4 &a, int c)
+{
+    return c == 0 ? a.x : c == 1 ? a.y : c == 2 ? a.z : a.w;
+}
+__device__ __forceinline__ float compv(const float4 &a, int c)
+{
+    return c == 0 ? a.x : c == 1 ? a.y : c == 2 ? a.z : a.w;
+}
+
+// Apply one operation to VEC rows of one replica's tile.  `rows` is the number
+// of full 256-element rows (VEC on the fast path); `count` bounds the ragged
+// path.  x/g point at the tile's first element in the caller's buffers
+// (storage dtype), xm/v/s at the tile's first element in the arenas.
+template <int VEC, int OP, bool BF16, int NT, bool FULL>
+__device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const void *gu, float *xm,
+                                           float *v, float *s, const float4 (&zt)[VEC], float wd,
+                                           uint32_t count, uint32_t lane)
+{
+    constexpr bool NEED_G = (OP == OP_STEP || OP == OP_STEP_MERGE);
+    constexpr bool NEED_V = NEED_G;
+    constexpr bool NEED_X = (OP != OP_INIT);
+    constexpr bool NEED_S = (OP == OP_MERGE || OP == OP_STEP_MERGE);
+    constexpr bool WRITE_X = (OP != OP_SNAPSHOT);
+    constexpr bool WRITE_V = NEED_V || OP == OP_INIT;
+    float *xf = BF16 ? xm : static_cast<float *>(xu);          // where the fp32 model lives
+    uint16_t *x16 = static_cast<uint16_t *>(xu);
+    const float *gf = static_cast<const float *>(gu);
+    const uint16_t *g16 = static_cast<const uint16_t *>(gu);
+    const bool write_s = (OP == OP_SNAPSHOT) || (NEED_S && a.resnap);
+
+    if constexpr (FULL) {
+        float4 x[VEC], vv[VEC], g[VEC], ss[VEC];
+        // all loads first: up to 4*VEC independent 128-bit loads in flight per lane
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const uint32_t e = j * 256u + lane * 4u;
+            if constexpr (NEED_G) g[j] = BF16 ? widen4(ld2<NT>(g16 + e)) : ld4<NT>(gf + e);
+            if constexpr (NEED_X) x[j] = ld4<NT>(xf + e);
+            if constexpr (OP == OP_INIT) x[j] = widen4(ld2<NT>(x16 + e));
+            if constexpr (NEED_V) vv[j] = ld4<NT>(v + e);
+            if constexpr (NEED_S) ss[j] = ld4<NT>(s + e);
+        }
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            const uint32_t e = j * 256u + lane * 4u;
+            if constexpr (NEED_G)
+                LASGD_FOR4(step_elem(comp(x[j], c), comp(vv[j], c), compv(g[j], c), wd, a.mu,
+                                     a.neg_lr, a.nesterov);)
+            if constexpr (NEED_S)
+                LASGD_FOR4(comp(x[j], c) = merge_elem(compv(x[j], c), compv(ss[j], c), compv(zt[j], c));)
+            if constexpr (OP == OP_INIT) vv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if constexpr (WRITE_V) st4<NT>(v + e, vv[j]);
+            if constexpr (WRITE_X) {
+                st4<NT>(xf + e, x[j]);
+                if constexpr (BF16 && OP != OP_INIT) st2<NT>(x16 + e, round4(x[j]));
+            }
+            if (write_s) st4<NT>(s + e, x[j]);
+        }
+    } else {
+        // ragged tile: same arithmetic, element by element where a 128-bit
+        // access would cross the end of the tensor
+#pragma unroll 1
+        for (int j = 0; j < VEC; ++j) {
+            const uint32_t e0 = j * 256u + lane * 4u;
+            if (e0 >= count) break;
+            const uint32_t n = (count - e0 < 4u) ? count - e0 : 4u;
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint32_t e = e0 + i;
+                float xe = 0.f, ve = 0.f, ge = 0.f, se = 0.f;
+                if constexpr (NEED_G) ge = BF16 ? bf16_widen(g16[e]) : gf[e];
+                if constexpr (NEED_X) xe = xf[e];
+                if constexpr (OP == OP_INIT) xe = bf16_widen(x16[e]);
+                if constexpr (NEED_V) ve = v[e];
+                if constexpr (NEED_S) se = s[e];
+                if constexpr (NEED_G) step_elem(xe, ve, ge, wd, a.mu, a.neg_lr, a.nesterov);
+                if constexpr (NEED_S) xe = merge_elem(xe, se, compv(zt[j], (int)i));
+                if constexpr (WRITE_V) v[e] = ve;
+                if constexpr (WRITE_X) {
+                    xf[e] = xe;
+                    if constexpr (BF16 && OP != OP_INIT) x16[e] = (uint16_t)bf16_round(xe);
+                }
+                if (write_s) s[e] = xe;
+            }
+        }
+    }
+}
+
+// Multi-tensor apply.  Work item = (tile, group of kper replicas); one wave
+// per item, items strided over the grid.  All table reads are wave-uniform.
+template <int VEC, int OP, bool BF16, int NT>
+__global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
+{
+    constexpr bool NEED_Z = (OP == OP_MERGE || OP == OP_STEP_MERGE);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * 4u;
+    for (uint32_t item = wave0; item < a.nitems; item += nwaves) {
+        const uint32_t tile = item / a.kgroups;
+        const uint32_t kg = item - tile * a.kgroups;
+        const Tile t = a.tiles[tile];
+        const bool full = (t.count == 256u * VEC);
+        float4 zt[VEC];
+        if constexpr (NEED_Z) {
+            const float *zp = a.z + t.aoff;
+            if (full) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) zt[j] = *reinterpret_cast<const float4 *>(zp + j * 256u + lane * 4u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    const uint32_t e0 = j * 256u + lane * 4u;
+                    zt[j].x = (e0 + 0u < t.count) ? zp[e0 + 0u] : 0.f;
+                    zt[j].y = (e0 + 1u < t.count) ? zp[e0 + 1u] : 0.f;
+                    zt[j].z = (e0 + 2u < t.count) ? zp[e0 + 2u] : 0.f;
+                    zt[j].w = (e0 + 3u < t.count) ? zp[e0 + 3u] : 0.f;
+                }
+            }
+        }
+        const uint32_t k0 = kg * a.kper;
+        const uint32_t k1 = (k0 + a.kper < a.K) ? k0 + a.kper : a.K;
+        for (uint32_t k = k0; k < k1; ++k) {
+            const size_t pi = (size_t)k * a.n_tensors + t.tensor;
+            const size_t esz = BF16 ? 2 : 4;
+            char *xu = static_cast<char *>(a.xptr[pi]) + t.toff * esz;
+            const char *gu = nullptr;
+            if constexpr (OP == OP_STEP || OP == OP_STEP_MERGE)
+                gu = static_cast<const char *>(a.gptr[pi]) + t.toff * esz;
+            const size_t ao = (size_t)k * a.npad + t.aoff;
+            float *xm = BF16 ? a.x32 + ao : nullptr;
+            if (full)
+                apply_tile<VEC, OP, BF16, NT, true>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane);
+            else
+                apply_tile<VEC, OP, BF16, NT, false>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane);
+        }
+    }
+}
+
+// ---- the mean (Sec. 3, Eq. 8) -----------------------------------------------
+// z[e] = (1/K) sum_k s[k][e], fp64 accumulation in replica order, one rounding.
+// The arenas are contiguous and padded with zeros, so this is a flat pass.
+struct AvgArgs {
+    const float *s;
+    float *z;
+    uint64_t npad;      // elements per replica, multiple of 4
+    uint64_t nvec;      // npad / 4
+    uint32_t K;
+    int32_t use_mul;    // K is a power of two: multiply by the exact reciprocal
+    double inv_k, k_as_double;
+};
+
+__device__ __forceinline__ float finish_mean(double acc, const AvgArgs &a)
+{
+    return a.use_mul ? (float)(acc * a.inv_k) : (float)(acc / a.k_as_double);
+}
+
+// SPLIT == 1: every lane owns one 128-bit column and walks all K replicas,
+// eight loads in flight at a time.
+template <int NT>
+__global__ __launch_bounds__(256) void average_kernel(const AvgArgs a)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < a.nvec; i += stride) {
+        const float *p = a.s + i * 4u;
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        uint32_t k = 0;
+        for (; k + 8u <= a.K; k += 8u) {
+            float4 r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
+            }
+        }
+        if (k + 4u <= a.K) {
+            float4 r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
+            }
+            k += 4u;
+        }
+        for (; k < a.K; ++k) {
+            float4 r = ld4<NT>(p + (uint64_t)k * a.npad);
+            a0 += (double)r.x; a1 += (double)r.y; a2 += (double)r.z; a3 += (double)r.w;
+        }
+        float4 out = make_float4(finish_mean(a0, a), finish_mean(a1, a), finish_mean(a2, a), finish_mean(a3, a));
+        st4<NT>(a.z + i * 4u, out);
+    }
+}
+
+// SPLIT in {2, 4}: the K replicas of one 256/SPLIT-column tile are divided
+// among SPLIT groups of waves; each group sums a contiguous range of replicas
+// in fp64, the partial sums meet in LDS and are added in group order.  More
+// independent load streams per column for large K; the result can differ from
+// the in-order sum only by fp64 rounding, i.e. in fp32 only at double-rounding ties.
+template <int SPLIT, int NT>
+__global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
+{
+    constexpr uint32_t COLS = 256u / SPLIT;             // 128-bit columns per workgroup pass
+    __shared__ double part[SPLIT][COLS][4];
+    const uint32_t g = threadIdx.x / COLS;              // which replica range
+    const uint32_t c = threadIdx.x % COLS;
+    const uint32_t kb = (uint32_t)(((uint64_t)a.K * g) / SPLIT);
+    const uint32_t ke = (uint32_t)(((uint64_t)a.K * (g + 1u)) / SPLIT);
+    const uint64_t ntile = (a.nvec + COLS - 1u) / COLS;
+    for (uint64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        const uint64_t i = tile * COLS + c;
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        if (i < a.nvec) {
+            const float *p = a.s + i * 4u;
+            uint32_t k = kb;
+            for (; k + 4u <= ke; k += 4u) {
+                float4 r[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
+                }
+            }
+            for (; k < ke; ++k) {
+                float4 r = ld4<NT>(p + (uint64_t)k * a.npad);
+                a0 += (double)r.x; a1 += (double)r.y; a2 += (double)r.z; a3 += (double)r.w;
+            }
+        }
+        part[g][c][0] = a0; part[g][c][1] = a1; part[g][c][2] = a2; part[g][c][3] = a3;
+        __syncthreads();
+        // 256 threads finish COLS*4 = 1024/SPLIT elements: 4/SPLIT each, consecutive
+        constexpr uint32_t PER = 4u / SPLIT;             // 2 or 1
+        const uint32_t e0 = threadIdx.x * PER;           // element within the tile
+        float outv[PER];
+#pragma unroll
+        for (uint32_t q = 0; q < PER; ++q) {
+            const uint32_t e = e0 + q;
+            double acc = 0.0;
+#pragma unroll
+            for (int gg = 0; gg < SPLIT; ++gg) acc += part[gg][e >> 2][e & 3u];
+            outv[q] = finish_mean(acc, a);
+        }
+        const uint64_t ebase = tile * COLS * 4u + e0;
+        if (ebase + PER <= a.npad) {
+            if constexpr (PER == 2) *reinterpret_cast<float2 *>(a.z + ebase) = make_float2(outv[0], outv[PER - 1]);
+            else a.z[ebase] = outv[0];
+        }
+        __syncthreads();
+    }
+}
+
+} // namespace lasgd

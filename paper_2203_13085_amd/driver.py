@@ -1,0 +1,123 @@
+"""Device-side plumbing around the binding: buffers, streams, Algorithm 1's loop.
+
+PyTorch is used for device memory and streams only.  Parameters and gradients
+of each replica live in one flat device buffer per replica, each tensor
+starting on a 512-byte boundary (the granularity a caching allocator would
+give separately allocated tensors); the library sees them as per-tensor
+pointers, exactly as it would see a real model's parameter list.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import Workload
+
+_ALIGN = 128  # elements
+
+
+def _offsets(numels: Sequence[int]) -> np.ndarray:
+    off, out = 0, []
+    for n in numels:
+        out.append(off)
+        off += (int(n) + _ALIGN - 1) // _ALIGN * _ALIGN
+    out.append(off)
+    return np.asarray(out, dtype=np.int64)
+
+
+class DeviceReplicas:
+    """K replicas' parameters and gradients on the GPU, bound to a LASGD context."""
+
+    def __init__(self, w: Workload, weight_decay: Optional[Sequence[float]] = None,
+                 side_stream: bool = True, device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the LASGD path runs only on the device")
+        self.w = w
+        self.dev = torch.device(device)
+        torch.cuda.set_device(self.dev)
+        self.numels = w.numels
+        self.off = _offsets(self.numels)
+        self.bf16 = w.storage == "bf16"
+        dt = torch.bfloat16 if self.bf16 else torch.float32
+        self.esize = 2 if self.bf16 else 4
+        self.main = torch.cuda.Stream(device=self.dev)
+        self.side = torch.cuda.Stream(device=self.dev) if side_stream else self.main
+        total = int(self.off[-1])
+        self.x = [torch.zeros(total, dtype=dt, device=self.dev) for _ in range(w.K)]
+        self.g = [torch.zeros(total, dtype=dt, device=self.dev) for _ in range(w.K)]
+        torch.cuda.synchronize()
+        wd = list(weight_decay) if weight_decay is not None else [w.weight_decay] * len(self.numels)
+        self.ctx = B.Context(w.K, self.numels, storage=B.BF16 if self.bf16 else B.F32,
+                             momentum=w.momentum, nesterov=w.nesterov, weight_decay=wd,
+                             main_stream=self.main.cuda_stream, side_stream=self.side.cuda_stream)
+        for k in range(w.K):
+            self.ctx.bind(k, [self.x[k].data_ptr() + int(o) * self.esize for o in self.off[:-1]],
+                          [self.g[k].data_ptr() + int(o) * self.esize for o in self.off[:-1]])
+        # packed <-> padded index map for uploads and downloads
+        idx = np.concatenate([np.arange(n, dtype=np.int64) + o for n, o in zip(self.numels, self.off[:-1])])
+        self._idx = torch.from_numpy(idx).to(self.dev)
+        self._contig = bool((idx == np.arange(idx.size)).all())
+
+    # ---- host <-> device (untimed plumbing) ---------------------------------
+    def _put(self, dst: torch.Tensor, flat: np.ndarray) -> None:
+        """flat: packed values over all tensors; fp32, or uint16 bf16 patterns."""
+        if self.bf16:
+            src = torch.from_numpy(np.ascontiguousarray(flat).view(np.int16)).to(self.dev).view(torch.bfloat16)
+        else:
+            src = torch.from_numpy(np.ascontiguousarray(flat, dtype=np.float32)).to(self.dev)
+        if self._contig:
+            dst[: src.numel()].copy_(src)
+        else:
+            dst[self._idx] = src
+
+    def _get(self, src: torch.Tensor) -> np.ndarray:
+        t = src[: self._idx.numel()] if self._contig else src[self._idx]
+        if self.bf16:
+            return t.view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()
+
+    def load_model(self, x0: np.ndarray) -> None:
+        """Every replica starts from the same model (Sec. 4)."""
+        self.ctx.sync()
+        for k in range(self.w.K):
+            self._put(self.x[k], x0)
+        torch.cuda.synchronize()
+        if self.bf16:
+            self.ctx.init_master()
+
+    def load_grads(self, grads: Sequence[np.ndarray]) -> None:
+        self.ctx.sync()
+        for k in range(self.w.K):
+            self._put(self.g[k], grads[k])
+        torch.cuda.synchronize()
+
+    def params(self, k: int) -> np.ndarray:
+        """The caller-visible parameters of replica k (fp32, or bf16 patterns)."""
+        self.ctx.sync()
+        return self._get(self.x[k])
+
+    # ---- Algorithm 1 with a fixed cadence ------------------------------------
+    def prologue(self, lr: float) -> None:
+        self.ctx.local_step(lr)      # steps 2-3
+        self.ctx.snapshot()          # step 4: send
+        self.ctx.average()           #         the All-Reduce starts on the side stream
+
+    def iteration(self, lr: float, tau: int, m: int, fused: bool = True) -> int:
+        """Steps 6-9 for one tick of the local clock; returns the new tau."""
+        tau += 1
+        if tau == m:
+            if fused:
+                self.ctx.step_merge(lr, True)
+            else:
+                self.ctx.local_step(lr)
+                self.ctx.merge(True)
+            self.ctx.average()
+            return 0
+        self.ctx.local_step(lr)
+        return tau
+
+    def close(self) -> None:
+        self.ctx.close()

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI,
+element by element after every step, on the same seeded inputs."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2203_13085_amd import binding as B
+from paper_2203_13085_amd import workloads as W
+from tests.parity_util import run_parity, say, packed_inputs, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+# ---- small ragged lists: several tiles, scalar tails, every launch shape ----
+@pytest.mark.parametrize("vec", [1, 2, 4])
+@pytest.mark.parametrize("fused", [True, False])
+def test_ragged_list_every_tile_shape(vec, fused):
+    w = W.small(K=3)
+    wd = [0.0 if i % 3 == 0 else 1e-3 * (i + 1) for i in range(len(w.numels))]
+    run_parity(w, weight_decay=wd, fused=fused, tuning=dict(vec=vec))
+
+
+@pytest.mark.parametrize("kper_step,kper_merge", [(1, 1), (2, 3), (5, 5), (3, 2)])
+def test_replica_grouping_does_not_change_results(kper_step, kper_merge):
+    w = W.small(K=5, numels=(3000, 7, 513, 256, 1025), m=3, T=7)
+    run_parity(w, tuning=dict(kper_step=kper_step, kper_merge=kper_merge))
+
+
+def test_heavy_ball_and_plain_sgd():
+    run_parity(W.small(K=4, nesterov=False))
+    run_parity(W.small(K=4, momentum=0.0, weight_decay=0.0, nesterov=False))
+
+
+def test_grid_cap_uses_the_stride_loop():
+    w = W.small(K=4, numels=(20000, 33, 4096))
+    run_parity(w, tuning=dict(max_blocks=3, avg_max_blocks=2, vec=1))
+
+
+def test_streaming_hints_do_not_change_results():
+    for nt in (1, 2, 3):
+        run_parity(W.small(K=3), tuning=dict(nontemporal=nt))
+
+
+def test_same_stream_for_both():
+    run_parity(W.small(K=3), side_stream=False)
+
+
+# ---- degenerate and extreme replica counts -----------------------------------
+def test_single_replica():
+    # K = 1: the mean is the sent model and the global update is the identity
+    run_parity(W.small(K=1, m=1, T=4))
+
+
+@pytest.mark.parametrize("K", [2, 7, 12, 64])
+def test_replica_counts_incl_non_powers_of_two_and_max(K):
+    run_parity(W.small(K=K, numels=(1030, 4, 257), m=2, T=4))
+
+
+def test_merge_every_step():
+    run_parity(W.small(K=4, m=1, T=5))
+
+
+def test_one_element_model():
+    run_parity(W.small(K=3, numels=(1,), m=2, T=4))
+
+
+# ---- the LDS-staged mean -------------------------------------------------------
+@pytest.mark.parametrize("K,split", [(16, 2), (16, 4), (32, 4), (5, 4), (3, 2)])
+def test_split_mean_staged_through_lds(K, split):
+    # summing replica ranges separately changes fp64 rounding only: z may differ
+    # from the in-order sum in the last fp32 bit at double-rounding ties, nowhere else
+    w = W.small(K=K, numels=(70000, 5, 1024), m=2, T=4)
+    ndiff = run_parity(w, tuning=dict(avg_split=split), z_exact=False)
+    assert ndiff <= 5
+
+
+# ---- bf16 storage -----------------------------------------------------------------
+@pytest.mark.parametrize("fused", [True, False])
+def test_bf16_storage(fused):
+    w = W.small(K=4, storage="bf16", m=2, T=6)
+    wd = [1e-4 if i % 2 else 0.0 for i in range(len(w.numels))]
+    run_parity(w, weight_decay=wd, fused=fused)
+
+
+def test_bf16_storage_vec4_k32():
+    run_parity(W.small(K=32, numels=(2048, 12, 999), storage="bf16", m=3, T=6), tuning=dict(vec=4, avg_split=1))
+
+
+# ---- configs[0] at full size: the oracle finishes in seconds -----------------------
+def test_config0_flat_1m_k4_full():
+    run_parity(W.config(0))
+    run_parity(W.config(0), fused=False)
+
+
+# ---- MobileNetV2-shaped list, reduced K: 158 tensors, many tiny ones ---------------
+def test_mobilenet_list_k4():
+    w = dataclasses.replace(W.config(3), K=4, T=3)
+    run_parity(w)
+
+
+# ---- protocol ------------------------------------------------------------------------
+def test_illegal_call_orders_are_refused():
+    import torch
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=2, numels=(300,))
+    dev = DeviceReplicas(w)
+    c = dev.ctx
+    try:
+        x0, grads = packed_inputs(w)
+        dev.load_model(x0)
+        dev.load_grads(grads(0))
+        for call in (lambda: c.merge(True), lambda: c.step_merge(0.1, True), lambda: c.average(),
+                     lambda: c.average_done(), lambda: c.init_master()):
+            with pytest.raises(B.LasgdError) as e:
+                call()
+            assert e.value.status == B.ERR_STATE
+        with pytest.raises(B.LasgdError) as e:
+            c.local_step(float("nan"))
+        assert e.value.status == B.ERR_INVALID
+        before = dev.params(0).copy()
+        c.local_step(0.1)
+        c.snapshot()
+        c.average()
+        for call in (lambda: c.average(), lambda: c.snapshot()):
+            with pytest.raises(B.LasgdError) as e:
+                call()
+            assert e.value.status == B.ERR_STATE
+        c.sync()
+        assert c.average_done()
+        c.merge(False)
+        with pytest.raises(B.LasgdError) as e:
+            c.average()           # s was not refreshed by that merge
+        assert e.value.status == B.ERR_STATE
+        c.snapshot()
+        c.average()
+        c.step_merge(0.1, True)
+        c.average()
+        c.sync()
+        # refused calls enqueued nothing: state equals the oracle's for the legal calls only
+        from oracle import lasgd_oracle as O32
+        o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, [w.weight_decay])
+        o.set_model(x0)
+        g = grads(0)
+        o.local_step(g, 0.1); o.snapshot(); o.average(); o.merge(False); o.snapshot(); o.average()
+        o.local_step(g, 0.1); o.merge(True); o.average()
+        for k in range(w.K):
+            assert_close(c.read_state(B.STATE_X, k), o.x[k], f"x[{k}]")
+        assert_close(c.read_state(B.STATE_Z), o.z, "z")
+        # argument errors of the probe
+        for args in ((9, 0, -1), (B.STATE_V, 5, -1), (B.STATE_V, 0, 3)):
+            with pytest.raises(B.LasgdError) as e:
+                c.read_state(*args)
+            assert e.value.status == B.ERR_INVALID
+        with pytest.raises(B.LasgdError) as e:
+            c.set_tuning(vec=3)
+        assert e.value.status == B.ERR_INVALID
+    finally:
+        dev.close()
+
+
+def test_unbound_and_misaligned():
+    import torch
+    c = B.Context(2, [64, 32], momentum=0.9, wd_scalar=0.0)
+    try:
+        x = torch.zeros(256, device="cuda")
+        g = torch.zeros(256, device="cuda")
+        with pytest.raises(B.LasgdError) as e:
+            c.local_step(0.1)
+        assert e.value.status == B.ERR_STATE
+        with pytest.raises(B.LasgdError) as e:
+            c.bind(0, [x.data_ptr() + 4, x.data_ptr() + 512], [g.data_ptr(), g.data_ptr() + 512])
+        assert e.value.status == B.ERR_INVALID
+        with pytest.raises(B.LasgdError) as e:
+            c.bind(2, [x.data_ptr(), x.data_ptr() + 512], [g.data_ptr(), g.data_ptr() + 512])
+        assert e.value.status == B.ERR_INVALID
+        c.bind(0, [x.data_ptr(), x.data_ptr() + 512], [g.data_ptr(), g.data_ptr() + 512])
+        with pytest.raises(B.LasgdError) as e:
+            c.local_step(0.1)     # replica 1 still unbound
+        assert e.value.status == B.ERR_STATE
+    finally:
+        c.close()
+
+
+def test_overlap_is_race_free_under_load():
+    """Local steps keep running on the main stream while the mean is computed
+    on the side stream; many cycles back to back without host synchronisation
+    must still equal the oracle (which has no concurrency at all)."""
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=8, numels=(1 << 20, 4096, 100), m=3, T=30)
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    try:
+        g = grads(1)
+        o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+        o.set_model(x0)
+        dev.load_model(x0)
+        dev.load_grads(g)
+        o.prologue(g, w.lr)
+        dev.prologue(w.lr)
+        tau = 0
+        for i in range(1, w.T + 1):          # same gradient buffer every step: no host sync inside the loop
+            o.iteration(g, w.lr, w.m)
+            tau = dev.iteration(w.lr, tau, w.m)
+        for k in range(w.K):
+            assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] after {w.T} unsynchronised steps")
+            assert_close(dev.ctx.read_state(B.STATE_S, k), o.s[k], f"s[{k}]")
+        assert_close(dev.ctx.read_state(B.STATE_Z), o.z, "z")
+    finally:
+        dev.close()

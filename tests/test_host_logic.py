@@ -1,0 +1,114 @@
+"""CPU-only checks of the product's host side: the shared library loads and
+exports what include/lasgd.h declares, argument validation happens before any
+device call, and the workload generator gives the published architectures."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2203_13085_amd import binding as B
+from paper_2203_13085_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lasgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lasgd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.load()
+    names = _declared()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in include/lasgd.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_binding_struct_layouts_match_header():
+    # field order and count of the two structs the binding mirrors
+    text = open(os.path.join(ROOT, "include", "lasgd.h")).read()
+    cfg = re.search(r"typedef struct \{([^{}]*)\} lasgd_config;", text, flags=re.S).group(1)
+    cfg = re.sub(r"/\*.*?\*/", "", cfg, flags=re.S)
+    fields = re.findall(r"(\w+)\s*;", cfg)
+    assert fields == [f for f, _ in B.Config._fields_]
+    tun = re.search(r"typedef struct \{([^{}]*)\} lasgd_tuning;", text, flags=re.S).group(1)
+    tun = re.sub(r"/\*.*?\*/", "", tun, flags=re.S)
+    assert re.findall(r"(\w+)\s*;", tun) == [f for f, _ in B.Tuning._fields_]
+    assert ctypes.sizeof(B.Tuning) == 28
+
+
+def _create(**kw):
+    L = B.load()
+    numel = kw.pop("numel", [16, 32])
+    arr = (ctypes.c_int64 * len(numel))(*numel) if numel is not None else None
+    wd = kw.pop("weight_decay", None)
+    wda = (ctypes.c_float * len(wd))(*wd) if wd is not None else None
+    cfg = B.Config(kw.pop("K", 2), kw.pop("n_tensors", len(numel) if numel else 0), arr,
+                   kw.pop("storage", 0), kw.pop("momentum", 0.9), 1, wda, kw.pop("wd_scalar", 0.0), None, None)
+    h = ctypes.c_void_p()
+    st = L.lasgd_create(ctypes.byref(cfg), ctypes.byref(h))
+    msg = L.lasgd_last_error(None).decode()
+    if st == B.OK:
+        L.lasgd_destroy(h)
+    else:
+        assert not h.value
+    return st, msg
+
+
+@pytest.mark.parametrize("kw", [dict(K=0), dict(K=65), dict(K=-3), dict(numel=[4, 0]), dict(numel=[-1]),
+                                dict(storage=7), dict(momentum=float("nan")), dict(momentum=-0.1),
+                                dict(wd_scalar=float("inf")), dict(weight_decay=[0.1, float("nan")]),
+                                dict(numel=None)])
+def test_create_rejects_bad_arguments_without_touching_the_device(kw):
+    st, msg = _create(**kw)
+    assert st == B.ERR_INVALID and msg
+
+
+def test_create_rejects_oversized_replica():
+    st, msg = _create(numel=[1 << 30, 1 << 30, 1 << 30])
+    assert st == B.ERR_UNSUPPORTED and "elements" in msg
+
+
+def test_null_arguments():
+    L = B.load()
+    assert L.lasgd_create(None, None) == B.ERR_INVALID
+    for f in ("lasgd_local_step",):
+        assert getattr(L, f)(None, 0.1) == B.ERR_INVALID
+    for f in ("lasgd_snapshot", "lasgd_average", "lasgd_sync", "lasgd_init_master"):
+        assert getattr(L, f)(None) == B.ERR_INVALID
+    assert L.lasgd_merge(None, 1) == B.ERR_INVALID
+    assert L.lasgd_step_merge(None, 0.1, 1) == B.ERR_INVALID
+    L.lasgd_destroy(None)    # allowed
+
+
+def test_shape_lists_match_published_architectures():
+    # tensor and parameter counts of the torchvision-style models these rules describe
+    for shapes, nt, npar in ((W.resnet_shapes(18), 62, 11689512), (W.resnet_shapes(50), 161, 25557032),
+                             (W.mobilenet_v2_shapes(), 158, 3504872)):
+        assert len(shapes) == nt
+        assert sum(W.numel(s) for _, s in shapes) == npar
+        assert all(W.numel(s) % 4 == 0 for _, s in shapes)
+    r50 = [W.numel(s) for _, s in W.resnet_shapes(50)]
+    assert min(r50) == 64 and max(r50) == 2359296
+    mb = [W.numel(s) for _, s in W.mobilenet_v2_shapes()]
+    assert min(mb) == 16 and max(mb) == 1280000
+
+
+def test_inputs_are_pure_functions_of_their_key():
+    w = W.config(1)
+    a = W.gradient_tensor(w, 3, 2, 5)
+    b = W.gradient_tensor(w, 3, 2, 5)
+    np.testing.assert_array_equal(a, b)
+    assert not np.array_equal(a, W.gradient_tensor(w, 3, 1, 5))
+    assert not np.array_equal(a, W.gradient_tensor(w, 4, 2, 5))
+    assert abs(float(a.std()) - 1e-3) < 2e-4
+    x0 = W.initial_tensor(w, 0)                     # 64x3x7x7 conv: He-normal, fan_in 147
+    assert abs(float(x0.std()) - (2 / 147) ** 0.5) < 0.01
+    assert np.all(W.initial_tensor(w, 1) == 1.0) and np.all(W.initial_tensor(w, 2) == 0.0)
+    bits = W.to_bf16_bits(a)
+    assert np.all(np.abs(W.bf16_bits_to_f32(bits) - a) <= np.abs(a) * 2.0 ** -8)
