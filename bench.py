@@ -79,6 +79,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="index into the baseline's config list")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the isolated per-kernel and serial legs")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies first (a kernel of known traffic, "
+                         "to calibrate profiler byte counters)")
     ap.add_argument("--tune", type=str, default="", help="k=v,k=v launch-shape knobs (lasgd_tuning fields)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -118,6 +121,15 @@ def main() -> int:
     def cycle(dev, tau=0):
         for _ in range(w.m):
             tau = dev.iteration(w.lr, tau, w.m)
+
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     alg = algorithmic_bytes(w.K, w.N, bf16)
     cycle_bytes = (w.m - 1) * alg["local_step"] + alg["step_merge"] + alg["average"]

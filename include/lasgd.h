@@ -87,7 +87,10 @@ typedef struct {
     int32_t max_blocks;    /* cap on workgroups per launch (grid-stride beyond it); <0 = no cap      */
     int32_t avg_split;     /* waves of a workgroup that share one tile's K replicas in average (1,2,4) */
     int32_t avg_max_blocks;/* cap on workgroups of the average kernel; <0 = no cap                   */
-    int32_t nontemporal;   /* bit 0: streaming loads, bit 1: streaming stores                        */
+    int32_t nontemporal;   /* 1: streaming hint on loads, 2: on stores, 3: both, 4: none             */
+    int32_t order_step;    /* work-item order of local_step / snapshot: 1 = tile-major (replicas of a
+                              tile adjacent), 2 = replica-major (tiles of a replica adjacent)        */
+    int32_t order_merge;   /* same for merge / step_merge                                            */
 } lasgd_tuning;
 
 /*

@@ -128,16 +128,23 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
     return LASGD_OK;
 }
 
+// Defaults from sweeps on MI355X over the five benchmark workloads: the finest
+// tile (one 128-bit vector per lane), one wave per (tile, replica), a grid that
+// covers all items, tiles of a replica adjacent in launch order, and the
+// streaming hint on every access except z once the state no longer fits the
+// 256 MB memory-side cache.  The split mean wins from K = 8 upwards.
 lasgd_tuning default_tuning(const lasgd_ctx &c)
 {
     lasgd_tuning t{};
-    t.vec = 2;
+    t.vec = 1;
     t.kper_step = 1;
-    t.kper_merge = c.K;
+    t.kper_merge = 1;
     t.max_blocks = -1;
-    t.avg_split = 1;
+    t.avg_split = c.K >= 8 ? 4 : 1;
     t.avg_max_blocks = -1;
-    t.nontemporal = 0;
+    t.nontemporal = ((uint64_t)c.K * c.npad * sizeof(float) >= (128ull << 20)) ? 3 : 0;
+    t.order_step = 2;
+    t.order_merge = 2;
     return t;
 }
 
@@ -196,6 +203,7 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
     a.mu = c->mu;
     a.nesterov = c->nesterov;
     a.resnap = resnap;
+    a.kmajor = (op == OP_MERGE || op == OP_STEP_MERGE) ? (c->tune.order_merge == 2) : (c->tune.order_step == 2);
     uint64_t blocks = (nitems + 3) / 4;                     // four waves per workgroup
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
     const dim3 grid((uint32_t)blocks);
@@ -516,6 +524,14 @@ lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
     if (t->nontemporal) {
         if (t->nontemporal < 0 || t->nontemporal > 4) return fail(c, LASGD_ERR_INVALID, "nontemporal outside 0..4");
         n.nontemporal = t->nontemporal == 4 ? 0 : t->nontemporal;      // 4 = switch the hints off again
+    }
+    if (t->order_step) {
+        if (t->order_step != 1 && t->order_step != 2) return fail(c, LASGD_ERR_INVALID, "order_step must be 1 or 2");
+        n.order_step = t->order_step;
+    }
+    if (t->order_merge) {
+        if (t->order_merge != 1 && t->order_merge != 2) return fail(c, LASGD_ERR_INVALID, "order_merge must be 1 or 2");
+        n.order_merge = t->order_merge;
     }
     lasgd_status st = lasgd_sync(c);
     if (st != LASGD_OK) return st;

@@ -45,6 +45,7 @@ struct ApplyArgs {
     uint32_t nitems;        // ntiles * kgroups
     float neg_lr, mu;
     int32_t nesterov, resnap;
+    int32_t kmajor;         // item order, see apply_kernel
 };
 
 // ---- 128-bit / 64-bit accesses, optionally with the streaming hint --------
@@ -197,11 +198,11 @@ __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const v
     } else {
         // ragged tile: same arithmetic, element by element where a 128-bit
         // access would cross the end of the tensor
-#pragma unroll 1
+        // (fully unrolled over j so that the z registers are never indexed at run time)
+#pragma unroll
         for (int j = 0; j < VEC; ++j) {
             const uint32_t e0 = j * 256u + lane * 4u;
-            if (e0 >= count) break;
-            const uint32_t n = (count - e0 < 4u) ? count - e0 : 4u;
+            const uint32_t n = (e0 >= count) ? 0u : (count - e0 < 4u) ? count - e0 : 4u;
             for (uint32_t i = 0; i < n; ++i) {
                 const uint32_t e = e0 + i;
                 float xe = 0.f, ve = 0.f, ge = 0.f, se = 0.f;
@@ -233,8 +234,14 @@ __global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
     const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
     const uint32_t nwaves = gridDim.x * 4u;
     for (uint32_t item = wave0; item < a.nitems; item += nwaves) {
-        const uint32_t tile = item / a.kgroups;
-        const uint32_t kg = item - tile * a.kgroups;
+        uint32_t tile, kg;
+        if (a.kmajor) {          // consecutive waves walk consecutive tiles of one replica group
+            kg = item / a.ntiles;
+            tile = item - kg * a.ntiles;
+        } else {                 // consecutive waves share a tile (and its z) across replica groups
+            tile = item / a.kgroups;
+            kg = item - tile * a.kgroups;
+        }
         const Tile t = a.tiles[tile];
         const bool full = (t.count == 256u * VEC);
         float4 zt[VEC];
