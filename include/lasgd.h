@@ -88,9 +88,11 @@ typedef struct {
     int32_t avg_split;     /* waves of a workgroup that share one tile's K replicas in average (1,2,4) */
     int32_t avg_max_blocks;/* cap on workgroups of the average kernel; <0 = no cap                   */
     int32_t nontemporal;   /* 1: streaming hint on loads, 2: on stores, 3: both, 4: none             */
-    int32_t order_step;    /* work-item order of local_step / snapshot: 1 = tile-major (replicas of a
-                              tile adjacent), 2 = replica-major (tiles of a replica adjacent)        */
-    int32_t order_merge;   /* same for merge / step_merge                                            */
+    int32_t chunk_step;    /* work-item order of local_step / snapshot: tiles are taken in chunks of this
+                              many; inside a chunk replica after replica.  1 = the replicas of a tile are
+                              adjacent; <0 = whole replica after whole replica                       */
+    int32_t chunk_merge;   /* same for merge / step_merge (a chunk's z tiles are reused K times within
+                              a short window)                                                        */
 } lasgd_tuning;
 
 /*

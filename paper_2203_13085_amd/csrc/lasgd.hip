@@ -132,7 +132,9 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
 // tile (one 128-bit vector per lane), one wave per (tile, replica), a grid that
 // covers all items, tiles of a replica adjacent in launch order, and the
 // streaming hint on every access except z once the state no longer fits the
-// 256 MB memory-side cache.  The split mean wins from K = 8 upwards.
+// 256 MB memory-side cache.  Items are ordered in chunks of 16384 tiles (16 MB
+// per array): long contiguous runs per replica, and the chunk's z is still
+// near when the next replica needs it.  The split mean wins from K = 8 upwards.
 lasgd_tuning default_tuning(const lasgd_ctx &c)
 {
     lasgd_tuning t{};
@@ -143,8 +145,8 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
     t.avg_split = c.K >= 8 ? 4 : 1;
     t.avg_max_blocks = -1;
     t.nontemporal = ((uint64_t)c.K * c.npad * sizeof(float) >= (128ull << 20)) ? 3 : 0;
-    t.order_step = 2;
-    t.order_merge = 2;
+    t.chunk_step = 16384;
+    t.chunk_merge = 16384;
     return t;
 }
 
@@ -203,7 +205,13 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
     a.mu = c->mu;
     a.nesterov = c->nesterov;
     a.resnap = resnap;
-    a.kmajor = (op == OP_MERGE || op == OP_STEP_MERGE) ? (c->tune.order_merge == 2) : (c->tune.order_step == 2);
+    int64_t chunk = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.chunk_merge : c->tune.chunk_step;
+    if (chunk < 1 || chunk > (int64_t)a.ntiles) chunk = a.ntiles;          // whole replica
+    a.chunk = (uint32_t)chunk;
+    const uint32_t nfull = a.ntiles / a.chunk;
+    a.full_items = nfull * a.chunk * a.kgroups;
+    a.tail_first = nfull * a.chunk;
+    a.tail_chunk = a.ntiles - a.tail_first ? a.ntiles - a.tail_first : 1u;
     uint64_t blocks = (nitems + 3) / 4;                     // four waves per workgroup
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
     const dim3 grid((uint32_t)blocks);
@@ -525,14 +533,8 @@ lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
         if (t->nontemporal < 0 || t->nontemporal > 4) return fail(c, LASGD_ERR_INVALID, "nontemporal outside 0..4");
         n.nontemporal = t->nontemporal == 4 ? 0 : t->nontemporal;      // 4 = switch the hints off again
     }
-    if (t->order_step) {
-        if (t->order_step != 1 && t->order_step != 2) return fail(c, LASGD_ERR_INVALID, "order_step must be 1 or 2");
-        n.order_step = t->order_step;
-    }
-    if (t->order_merge) {
-        if (t->order_merge != 1 && t->order_merge != 2) return fail(c, LASGD_ERR_INVALID, "order_merge must be 1 or 2");
-        n.order_merge = t->order_merge;
-    }
+    if (t->chunk_step) n.chunk_step = t->chunk_step < 0 ? -1 : t->chunk_step;
+    if (t->chunk_merge) n.chunk_merge = t->chunk_merge < 0 ? -1 : t->chunk_merge;
     lasgd_status st = lasgd_sync(c);
     if (st != LASGD_OK) return st;
     if (n.vec != c->tune.vec) {

@@ -45,7 +45,10 @@ struct ApplyArgs {
     uint32_t nitems;        // ntiles * kgroups
     float neg_lr, mu;
     int32_t nesterov, resnap;
-    int32_t kmajor;         // item order, see apply_kernel
+    uint32_t chunk;         // item order, see apply_kernel
+    uint32_t full_items;    // (ntiles / chunk) * chunk * kgroups
+    uint32_t tail_first;    // first tile of the last, shorter chunk
+    uint32_t tail_chunk;    // its length (>= 1 even when unused)
 };
 
 // ---- 128-bit / 64-bit accesses, optionally with the streaming hint --------
@@ -234,13 +237,22 @@ __global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
     const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
     const uint32_t nwaves = gridDim.x * 4u;
     for (uint32_t item = wave0; item < a.nitems; item += nwaves) {
+        // Item order: tiles are taken in chunks of a.chunk; inside a chunk the items run
+        // replica group by replica group, so that each replica's arrays are swept in
+        // contiguous runs of a.chunk tiles while the chunk's z tiles are reused K times
+        // within a short window (chunk = 1: the replicas of one tile are adjacent;
+        // chunk = ntiles: one replica after the other).
         uint32_t tile, kg;
-        if (a.kmajor) {          // consecutive waves walk consecutive tiles of one replica group
-            kg = item / a.ntiles;
-            tile = item - kg * a.ntiles;
-        } else {                 // consecutive waves share a tile (and its z) across replica groups
-            tile = item / a.kgroups;
-            kg = item - tile * a.kgroups;
+        if (item < a.full_items) {
+            const uint32_t per = a.chunk * a.kgroups;
+            const uint32_t ch = item / per;
+            const uint32_t r = item - ch * per;
+            kg = r / a.chunk;
+            tile = ch * a.chunk + (r - kg * a.chunk);
+        } else {
+            const uint32_t r = item - a.full_items;
+            kg = r / a.tail_chunk;
+            tile = a.tail_first + (r - kg * a.tail_chunk);
         }
         const Tile t = a.tiles[tile];
         const bool full = (t.count == 256u * VEC);

@@ -27,6 +27,13 @@ def test_replica_grouping_does_not_change_results(kper_step, kper_merge):
     run_parity(w, tuning=dict(kper_step=kper_step, kper_merge=kper_merge))
 
 
+@pytest.mark.parametrize("chunk", [1, 2, 3, 7, 16, 1000, -1])
+def test_item_order_does_not_change_results(chunk):
+    # 12 + 1 + 3 + 1 + 5 = 22 tiles at vec=1: chunk sizes that divide it, that leave a tail, and beyond it
+    w = W.small(K=3, numels=(3000, 7, 513, 256, 1025), m=2, T=4)
+    run_parity(w, tuning=dict(chunk_step=chunk, chunk_merge=chunk, kper_merge=2 if chunk == 3 else 1))
+
+
 def test_heavy_ball_and_plain_sgd():
     run_parity(W.small(K=4, nesterov=False))
     run_parity(W.small(K=4, momentum=0.0, weight_decay=0.0, nesterov=False))
