@@ -25,6 +25,15 @@
  * torch, mean vs exactly rounded sum.  Every function below is covered by at
  * least one of them; none is "parity unpinned".
  *
+ * Extensions beyond the fixed-cadence algorithm (each pinned in
+ * tests/test_oracle_ext_pins.py):
+ *   - elastic coefficients alpha, beta of Sec. 3 (Eq. 5-6) in the asynchronous
+ *     setting of Sec. 4
+ *   - the mean over a subset of replicas (the partial All-Reduce of Sec. 6)
+ *   - the SGD All-Reduce comparator of Sec. 2 / Table 1: one step on the mean gradient
+ * Replica subsets and per-replica step counts / learning rates are handled by
+ * the Python driver, which simply skips the replicas that are not taking part.
+ *
  * Build: gcc -O2 -ffp-contract=off -fPIC -shared (contraction must stay off
  * so that only the fmaf() calls written here fuse).
  */
@@ -150,4 +159,94 @@ void lasgd_oracle_widen_bf16(float *x32, const uint16_t *x16, int64_t n)
 {
     for (int64_t e = 0; e < n; ++e)
         x32[e] = lasgd_oracle_bf16_widen(x16[e]);
+}
+
+/* ---- elastic averaging with general alpha, beta (Sec. 3, Eq. 5-6) ------- */
+/*
+ * Centre update, Eq. 5 read with beta_t = P*gamma_t:  z <- (1-beta)*z + beta*mean_k s[k].
+ * The mean is taken over the models sent for this global update (the indexing
+ * of Eq. 8 and Algorithm 1, not the one-step lag Eq. 5 prints).  fp64
+ * throughout, one rounding to fp32.  beta = 1 is lasgd_oracle_average.
+ */
+void lasgd_oracle_average_elastic(float *z, const float *const *s, int32_t K, int64_t n, float beta)
+{
+    const double b = (double)beta, one_minus_b = 1.0 - (double)beta;
+    for (int64_t e = 0; e < n; ++e) {
+        double acc = 0.0;
+        for (int32_t k = 0; k < K; ++k)
+            acc += (double)s[k][e];
+        double mean = acc / (double)K;
+        double keep = one_minus_b * (double)z[e];
+        double pull = b * mean;
+        z[e] = (float)(keep + pull);
+    }
+}
+
+/*
+ * Local side, Eq. 6 carried to the asynchronous setting: the elastic pull
+ * alpha*(z_t - x^i_t) is measured at the model that was sent and applied to the
+ * model as it is now:  x <- x + alpha*(z - s).  With one step in flight
+ * (x = s - eta*g) this is Eq. 6, alpha*z + (1-alpha)*s - eta*g; with alpha = 1
+ * it is step 9a of Algorithm 1 up to rounding order (lasgd_oracle_merge_f32
+ * keeps the printed parenthesisation for that case).
+ */
+void lasgd_oracle_merge_elastic_f32(float *x, float *s, const float *z, int64_t n, float alpha,
+                                    int resnapshot)
+{
+    for (int64_t e = 0; e < n; ++e) {
+        float pull = z[e] - s[e];
+        float xn = fmaf(alpha, pull, x[e]);
+        x[e] = xn;
+        if (resnapshot)
+            s[e] = xn;
+    }
+}
+
+void lasgd_oracle_merge_elastic_bf16(float *x32, uint16_t *x16, float *s, const float *z, int64_t n,
+                                     float alpha, int resnapshot)
+{
+    for (int64_t e = 0; e < n; ++e) {
+        float pull = z[e] - s[e];
+        float xn = fmaf(alpha, pull, x32[e]);
+        x32[e] = xn;
+        x16[e] = lasgd_oracle_bf16_rne(xn);
+        if (resnapshot)
+            s[e] = xn;
+    }
+}
+
+/* ---- SGD All-Reduce comparator (Sec. 2; "SGD-AR" of Table 1) ------------ */
+/*
+ * All workers average their mini-batch gradients and every worker applies the
+ * same step: gbar = (1/K) sum_k g[k] (fp64 in replica order, one rounding to
+ * fp32), then the local update of Sec. 5.2 with gbar on each replica.
+ */
+void lasgd_oracle_mean_gradient_f32(float *gbar, const float *const *g, int32_t K, int64_t n)
+{
+    for (int64_t e = 0; e < n; ++e) {
+        double acc = 0.0;
+        for (int32_t k = 0; k < K; ++k)
+            acc += (double)g[k][e];
+        gbar[e] = (float)(acc / (double)K);
+    }
+}
+
+void lasgd_oracle_mean_gradient_bf16(float *gbar, const uint16_t *const *g16, int32_t K, int64_t n)
+{
+    for (int64_t e = 0; e < n; ++e) {
+        double acc = 0.0;
+        for (int32_t k = 0; k < K; ++k)
+            acc += (double)lasgd_oracle_bf16_widen(g16[k][e]);
+        gbar[e] = (float)(acc / (double)K);
+    }
+}
+
+/* the bf16-storage local step fed an fp32 gradient (the mean above) */
+void lasgd_oracle_local_step_bf16_g32(float *x32, uint16_t *x16, float *v, const float *g, int64_t n,
+                                      float lr, float mu, float wd, int nesterov)
+{
+    for (int64_t e = 0; e < n; ++e) {
+        step_one(&x32[e], &v[e], g[e], lr, mu, wd, nesterov);
+        x16[e] = lasgd_oracle_bf16_rne(x32[e]);
+    }
 }

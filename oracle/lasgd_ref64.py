@@ -31,6 +31,7 @@ class Ref64:
         self.v = np.zeros((K, self.N))
         self.s = np.zeros((K, self.N))
         self.z = np.zeros(self.N)
+        self.center_valid = False
         self.tau = 0
         self.t = 0
 
@@ -38,23 +39,48 @@ class Ref64:
         self.x[:] = np.asarray(x0, dtype=np.float64)[None, :]
         self.v[:] = 0.0
 
-    def local_step(self, grads: Sequence[np.ndarray], lr: float) -> None:
+    def _sel(self, mask) -> np.ndarray:
+        """Boolean selector of the replicas taking part (all when mask is None)."""
+        if mask is None:
+            return np.ones(self.K, dtype=bool)
+        return np.array([(int(mask) >> k) & 1 == 1 for k in range(self.K)])
+
+    def local_step(self, grads: Sequence[np.ndarray], lr, mask=None) -> None:
+        sel = self._sel(mask)
+        lrs = np.full(self.K, float(lr)) if np.isscalar(lr) else np.asarray(lr, dtype=np.float64)
         g = np.stack([np.asarray(a, dtype=np.float64) for a in grads])
         g = g + self.wd[None, :] * self.x           # L2 decay joins the gradient
-        self.v = self.mu * self.v + g               # momentum buffer, zero dampening
-        d = g + self.mu * self.v if self.nesterov else self.v
-        self.x = self.x - lr * d
+        v = self.mu * self.v + g                    # momentum buffer, zero dampening
+        d = g + self.mu * v if self.nesterov else v
+        x = self.x - lrs[:, None] * d
+        self.v = np.where(sel[:, None], v, self.v)  # idle replicas keep their state
+        self.x = np.where(sel[:, None], x, self.x)
 
-    def snapshot(self) -> None:
-        self.s = self.x.copy()
+    def snapshot(self, mask=None) -> None:
+        sel = self._sel(mask)
+        self.s = np.where(sel[:, None], self.x, self.s)
 
-    def average(self) -> None:
-        self.z = self.s.sum(axis=0) / self.K
+    def average(self, mask=None, beta: float = 1.0) -> None:
+        sel = self._sel(mask)
+        mean = self.s[sel].sum(axis=0) / int(sel.sum())
+        if not self.center_valid:
+            beta = 1.0                              # the first mean initialises the centre
+        self.center_valid = True
+        self.z = (1.0 - beta) * self.z + beta * mean
 
-    def merge(self, resnapshot: bool = True) -> None:
-        self.x = self.z[None, :] + (self.x - self.s)
+    def merge(self, resnapshot: bool = True, mask=None, alpha: float = 1.0) -> None:
+        sel = self._sel(mask)
+        if alpha == 1.0:
+            x = self.z[None, :] + (self.x - self.s)
+        else:
+            x = self.x + alpha * (self.z[None, :] - self.s)
+        self.x = np.where(sel[:, None], x, self.x)
         if resnapshot:
-            self.s = self.x.copy()
+            self.s = np.where(sel[:, None], self.x, self.s)
+
+    def sgd_ar_step(self, grads: Sequence[np.ndarray], lr: float) -> None:
+        gbar = np.stack([np.asarray(a, dtype=np.float64) for a in grads]).mean(axis=0)
+        self.local_step([gbar] * self.K, lr)
 
     def prologue(self, grads0, lr: float) -> None:
         self.local_step(grads0, lr)
@@ -85,4 +111,33 @@ def run_schedule(o: Ref64, x0: np.ndarray, grads: Callable[[int], List[np.ndarra
         o.iteration(grads(i), lr, m)
         if after:
             after(i, o)
+    return o
+
+
+def run_dynamic(o: Ref64, x0, grads, lr, rounds, after=None) -> Ref64:
+    """Algorithm 1 with scripted per-replica step counts per All-Reduce; see the
+    fp32 oracle's run_dynamic for the meaning of the arguments."""
+    K = o.K
+    o.set_model(x0)
+    tick = 0
+    o.local_step(grads(0), [lr(k, 0) for k in range(K)])
+    clock = [1] * K
+    o.snapshot()
+    o.average()
+    if after:
+        after(tick, o)
+    for counts in rounds:
+        last = max(counts) - 1
+        for j in range(last + 1):
+            tick += 1
+            active = [k for k in range(K) if counts[k] > j]
+            o.local_step(grads(tick), [lr(k, clock[k]) for k in range(K)], mask=sum(1 << k for k in active))
+            for k in active:
+                clock[k] += 1
+            if j == last:
+                o.merge(True)
+                o.average()
+                o.t += 1
+            if after:
+                after(tick, o)
     return o
