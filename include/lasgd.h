@@ -170,6 +170,64 @@ lasgd_status lasgd_merge(lasgd_ctx *ctx, int32_t resnapshot);
  */
 lasgd_status lasgd_step_merge(lasgd_ctx *ctx, float lr, int32_t resnapshot);
 
+/* ---- extended calls: replicas at their own pace, partial All-Reduce, elastic
+ *      coefficients, the SGD All-Reduce comparator ----------------------------
+ *
+ * In Algorithm 1 every node runs its own loop: it takes between 1 and tau_max
+ * local steps per All-Reduce, with a step size indexed by its own clock, and
+ * nodes merge "asynchronously from each other" (Sec. 4).  With K nodes batched
+ * on one GPU this becomes a bit mask per call (bit k = replica k takes part)
+ * and a step size per replica.  The same masks express the partial All-Reduce
+ * the paper proposes as future work (Sec. 6): the mean is taken over the
+ * participants only and divided by their number; a replica that sits a round
+ * out neither sends nor merges in it.  Order rules, per replica: it must have
+ * sent (snapshot, or merge with resnapshot) before it is averaged; it may not
+ * be snapshotted while a mean it takes part in is unmerged; a new mean cannot
+ * start before every participant of the previous one has merged (one z buffer).
+ * Each plain call above equals its _ex form with all K bits set and equal step sizes.
+ */
+
+/* Local update of the replicas in `mask` (may be empty); lr: host [K], entry k
+ * read only if bit k is set.  Errors: as lasgd_local_step, plus INVALID for a
+ * NULL array, a bit beyond K or a non-finite entry. */
+lasgd_status lasgd_local_step_ex(lasgd_ctx *ctx, const float *lr, uint64_t mask);
+
+/* s[k] <- x[k] for the replicas in `mask` (non-empty).
+ * Errors: as lasgd_snapshot (STATE only if the pending mean involves one of them). */
+lasgd_status lasgd_snapshot_ex(lasgd_ctx *ctx, uint64_t mask);
+
+/* z <- mean over the replicas in `mask` (non-empty) of s[k]; with beta != 1
+ * (lasgd_set_elastic) blended into the previous centre.  Side stream.
+ * Errors: as lasgd_average, per participant. */
+lasgd_status lasgd_average_ex(lasgd_ctx *ctx, uint64_t mask);
+
+/* Global update of the replicas in `mask` (non-empty subset of the pending
+ * mean's participants that have not merged yet). */
+lasgd_status lasgd_merge_ex(lasgd_ctx *ctx, uint64_t mask, int32_t resnapshot);
+
+/* One pass in which the replicas in step_mask take a local update (lr: host [K])
+ * and those in merge_mask (non-empty) then take the global update; a replica may
+ * be in either, both or neither. */
+lasgd_status lasgd_step_merge_ex(lasgd_ctx *ctx, const float *lr, uint64_t step_mask,
+                                 uint64_t merge_mask, int32_t resnapshot);
+
+/*
+ * Elastic coefficients of Sec. 3 (Eq. 5-6; alpha = eta*rho, beta = P*gamma) for
+ * all later calls: the mean becomes z <- (1-beta) z + beta mean_k s[k] (the first
+ * mean after create initialises z), the global update x <- x + alpha (z - s).
+ * alpha = beta = 1 (the default) is Algorithm 1 exactly.
+ * Errors: INVALID (a value outside [0, 1] or not a number).
+ */
+lasgd_status lasgd_set_elastic(lasgd_ctx *ctx, float alpha, float beta);
+
+/*
+ * The SGD All-Reduce comparator (Sec. 2; "SGD-AR" in Table 1): average the K
+ * gradients (fp64 accumulate, one rounding) and let every replica take the local
+ * update with the mean gradient, in one pass.  Main stream; touches x, v only.
+ * Errors: as lasgd_local_step.
+ */
+lasgd_status lasgd_sgd_ar_step(lasgd_ctx *ctx, float lr);
+
 /*
  * Parity probe: wait for both streams, then copy one array to host memory as
  * fp32.  tensor >= 0: that tensor of replica k, n must equal numel[tensor];

@@ -25,7 +25,9 @@ _STATUS_NAMES = ["OK", "ERR_INVALID", "ERR_STATE", "ERR_ALLOC", "ERR_HIP", "ERR_
 EXPORTS = ["lasgd_create", "lasgd_bind", "lasgd_init_master", "lasgd_local_step", "lasgd_snapshot",
            "lasgd_average", "lasgd_average_done", "lasgd_merge", "lasgd_step_merge",
            "lasgd_read_state", "lasgd_sync", "lasgd_set_tuning", "lasgd_get_tuning",
-           "lasgd_last_error", "lasgd_destroy"]
+           "lasgd_last_error", "lasgd_destroy", "lasgd_local_step_ex", "lasgd_snapshot_ex",
+           "lasgd_average_ex", "lasgd_merge_ex", "lasgd_step_merge_ex", "lasgd_set_elastic",
+           "lasgd_sgd_ar_step"]
 
 
 class LasgdError(RuntimeError):
@@ -77,6 +79,14 @@ def load() -> ctypes.CDLL:
     L.lasgd_sync.argtypes = [P]
     L.lasgd_set_tuning.argtypes = [P, ctypes.POINTER(Tuning)]
     L.lasgd_get_tuning.argtypes = [P, ctypes.POINTER(Tuning)]
+    u64, f32p = ctypes.c_uint64, ctypes.POINTER(ctypes.c_float)
+    L.lasgd_local_step_ex.argtypes = [P, f32p, u64]
+    L.lasgd_snapshot_ex.argtypes = [P, u64]
+    L.lasgd_average_ex.argtypes = [P, u64]
+    L.lasgd_merge_ex.argtypes = [P, u64, i32]
+    L.lasgd_step_merge_ex.argtypes = [P, f32p, u64, u64, i32]
+    L.lasgd_set_elastic.argtypes = [P, f32, f32]
+    L.lasgd_sgd_ar_step.argtypes = [P, f32]
     L.lasgd_last_error.argtypes = [P]
     L.lasgd_last_error.restype = ctypes.c_char_p
     L.lasgd_destroy.argtypes = [P]
@@ -163,6 +173,32 @@ class Context:
 
     def step_merge(self, lr: float, resnapshot: bool = True) -> None:
         self._check(self._L.lasgd_step_merge(self._h, lr, int(resnapshot)))
+
+    def _lrs(self, lr):
+        vals = [float(lr)] * self.K if np.isscalar(lr) else [float(a) for a in lr]
+        assert len(vals) == self.K
+        return (ctypes.c_float * self.K)(*vals)
+
+    def local_step_ex(self, lr, mask: int) -> None:
+        self._check(self._L.lasgd_local_step_ex(self._h, self._lrs(lr), mask))
+
+    def snapshot_ex(self, mask: int) -> None:
+        self._check(self._L.lasgd_snapshot_ex(self._h, mask))
+
+    def average_ex(self, mask: int) -> None:
+        self._check(self._L.lasgd_average_ex(self._h, mask))
+
+    def merge_ex(self, mask: int, resnapshot: bool = True) -> None:
+        self._check(self._L.lasgd_merge_ex(self._h, mask, int(resnapshot)))
+
+    def step_merge_ex(self, lr, step_mask: int, merge_mask: int, resnapshot: bool = True) -> None:
+        self._check(self._L.lasgd_step_merge_ex(self._h, self._lrs(lr), step_mask, merge_mask, int(resnapshot)))
+
+    def set_elastic(self, alpha: float, beta: float) -> None:
+        self._check(self._L.lasgd_set_elastic(self._h, alpha, beta))
+
+    def sgd_ar_step(self, lr: float) -> None:
+        self._check(self._L.lasgd_sgd_ar_step(self._h, lr))
 
     def read_state(self, which: int, k: int = 0, tensor: int = -1) -> np.ndarray:
         # an out-of-range tensor index is the library's to refuse

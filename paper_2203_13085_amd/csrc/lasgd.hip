@@ -55,11 +55,14 @@ struct lasgd_ctx {
     std::vector<char> bound;
     int32_t n_bound = 0;
 
-    // protocol state
+    // protocol state (bit k = replica k)
     bool master_ready = false;   // bf16: master copy initialised
-    bool snap_valid = false;     // s holds the models to be averaged next
-    bool avg_pending = false;    // an average was launched and not yet merged
+    uint64_t all = 0;            // every replica
+    uint64_t snap_mask = 0;      // s[k] holds a model that may be averaged next
+    uint64_t pending_mask = 0;   // participants of the launched mean that have not merged yet
     bool avg_ever = false;
+    bool center_valid = false;   // z has been computed at least once
+    float alpha = 1.f, beta = 1.f;   // elastic coefficients (Sec. 3, Eq. 5-6); 1, 1 = Algorithm 1
 
     lasgd_tuning tune{};
     std::string err;
@@ -151,8 +154,13 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
 }
 
 template <int VEC, int OP, bool BF16>
-hipError_t launch_nt(const ApplyArgs &a, dim3 grid, hipStream_t st, int nt)
+hipError_t launch_nt(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int nt)
 {
+    if (xa) {      // extended variants: hints all on or all off
+        if (nt & 3) hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 3>), grid, dim3(256), 0, st, a, *xa);
+        else hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 0>), grid, dim3(256), 0, st, a, *xa);
+        return hipGetLastError();
+    }
     switch (nt & 3) {
     case 0: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 0>), grid, dim3(256), 0, st, a); break;
     case 1: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 1>), grid, dim3(256), 0, st, a); break;
@@ -163,25 +171,23 @@ hipError_t launch_nt(const ApplyArgs &a, dim3 grid, hipStream_t st, int nt)
 }
 
 template <int OP, bool BF16>
-hipError_t launch_vec(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt)
+hipError_t launch_vec(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int vec, int nt)
 {
     switch (vec) {
-    case 1: return launch_nt<1, OP, BF16>(a, grid, st, nt);
-    case 2: return launch_nt<2, OP, BF16>(a, grid, st, nt);
-    default: return launch_nt<4, OP, BF16>(a, grid, st, nt);
+    case 1: return launch_nt<1, OP, BF16>(a, xa, grid, st, nt);
+    case 2: return launch_nt<2, OP, BF16>(a, xa, grid, st, nt);
+    default: return launch_nt<4, OP, BF16>(a, xa, grid, st, nt);
     }
 }
 
 template <int OP>
-hipError_t launch_op(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt, bool bf16)
+hipError_t launch_op(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int vec, int nt, bool bf16)
 {
-    return bf16 ? launch_vec<OP, true>(a, grid, st, vec, nt) : launch_vec<OP, false>(a, grid, st, vec, nt);
+    return bf16 ? launch_vec<OP, true>(a, xa, grid, st, vec, nt) : launch_vec<OP, false>(a, xa, grid, st, vec, nt);
 }
 
-// Enqueue one multi-tensor pass on the main stream.
-lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
+void fill_common(const lasgd_ctx *c, ApplyArgs &a)
 {
-    ApplyArgs a{};
     a.tiles = c->tiles;
     a.xptr = c->xptr;
     a.gptr = c->gptr;
@@ -193,6 +199,16 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
     a.ntiles = c->ntiles;
     a.K = (uint32_t)c->K;
     a.n_tensors = (uint32_t)c->n_tensors;
+    a.mu = c->mu;
+    a.nesterov = c->nesterov;
+}
+
+// Enqueue one multi-tensor pass on the main stream.  xa == nullptr: every
+// replica takes part, one step size, alpha = 1 (the plain kernels).
+lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const ExtArgs *xa = nullptr)
+{
+    ApplyArgs a{};
+    fill_common(c, a);
     int kper = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.kper_merge : c->tune.kper_step;
     if (kper < 1) kper = 1;
     if (kper > c->K) kper = c->K;
@@ -202,8 +218,6 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
     if (nitems == 0 || nitems > 0x7fffffffull) return fail(c, LASGD_ERR_UNSUPPORTED, "work-item count %llu out of range", (unsigned long long)nitems);
     a.nitems = (uint32_t)nitems;
     a.neg_lr = -lr;
-    a.mu = c->mu;
-    a.nesterov = c->nesterov;
     a.resnap = resnap;
     int64_t chunk = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.chunk_merge : c->tune.chunk_step;
     if (chunk < 1 || chunk > (int64_t)a.ntiles) chunk = a.ntiles;          // whole replica
@@ -216,30 +230,69 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap)
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
     const dim3 grid((uint32_t)blocks);
     const bool bf16 = c->storage == LASGD_BF16;
+    const int vec = c->tune.vec, nt = c->tune.nontemporal;
     hipError_t e = hipSuccess;
     switch (op) {
-    case OP_STEP: e = launch_op<OP_STEP>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
-    case OP_MERGE: e = launch_op<OP_MERGE>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
-    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
-    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, grid, c->main, c->tune.vec, c->tune.nontemporal, bf16); break;
-    case OP_INIT: e = launch_vec<OP_INIT, true>(a, grid, c->main, c->tune.vec, c->tune.nontemporal); break;
+    case OP_STEP: e = launch_op<OP_STEP>(a, xa, grid, c->main, vec, nt, bf16); break;
+    case OP_MERGE: e = launch_op<OP_MERGE>(a, xa, grid, c->main, vec, nt, bf16); break;
+    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, xa, grid, c->main, vec, nt, bf16); break;
+    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, xa, grid, c->main, vec, nt, bf16); break;
+    case OP_INIT: e = launch_vec<OP_INIT, true>(a, nullptr, grid, c->main, vec, nt); break;
     default: return fail(c, LASGD_ERR_INVALID, "unknown op %d", op);
     }
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return LASGD_OK;
 }
 
-lasgd_status enqueue_average(lasgd_ctx *c)
+template <bool BF16>
+hipError_t launch_sgd_ar(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt)
+{
+#define LASGD_AR(V)                                                                             \
+    do {                                                                                        \
+        if (nt & 3) hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 3>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 0>), grid, dim3(256), 0, st, a);        \
+    } while (0)
+    if (vec == 1) LASGD_AR(1);
+    else if (vec == 2) LASGD_AR(2);
+    else LASGD_AR(4);
+#undef LASGD_AR
+    return hipGetLastError();
+}
+
+template <bool EXT>
+hipError_t launch_average(const AvgArgs &a, dim3 grid, hipStream_t st, int split, bool nt)
+{
+    if (split == 1) {
+        if (nt) hipLaunchKernelGGL((average_kernel<3, EXT>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((average_kernel<0, EXT>), grid, dim3(256), 0, st, a);
+    } else if (split == 2) {
+        if (nt) hipLaunchKernelGGL((average_split_kernel<2, 3, EXT>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((average_split_kernel<2, 0, EXT>), grid, dim3(256), 0, st, a);
+    } else {
+        if (nt) hipLaunchKernelGGL((average_split_kernel<4, 3, EXT>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((average_split_kernel<4, 0, EXT>), grid, dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+// Enqueue the mean of the replicas in `mask` on the side stream.
+lasgd_status enqueue_average(lasgd_ctx *c, uint64_t mask, bool elastic)
 {
     AvgArgs a{};
     a.s = c->s;
     a.z = c->z;
     a.npad = c->npad;
     a.nvec = c->npad / 4;
-    a.K = (uint32_t)c->K;
-    a.use_mul = is_pow2((uint32_t)c->K) ? 1 : 0;
-    a.inv_k = 1.0 / (double)c->K;
-    a.k_as_double = (double)c->K;
+    uint32_t kp = 0;
+    for (int k = 0; k < c->K; ++k)
+        if ((mask >> k) & 1ull) a.idx[kp++] = (uint8_t)k;
+    a.K = kp;
+    a.use_mul = is_pow2(kp) ? 1 : 0;
+    a.inv_k = 1.0 / (double)kp;
+    a.k_as_double = (double)kp;
+    a.elastic = elastic ? 1 : 0;
+    a.beta = (double)c->beta;
+    a.one_minus_beta = 1.0 - (double)c->beta;
     const int split = c->tune.avg_split;
     const uint64_t cols = 256u / (uint32_t)split;
     uint64_t blocks = (a.nvec + cols - 1) / cols;
@@ -247,17 +300,8 @@ lasgd_status enqueue_average(lasgd_ctx *c)
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
     const dim3 grid((uint32_t)blocks);
     const bool nt = (c->tune.nontemporal & 1) != 0;
-    if (split == 1) {
-        if (nt) hipLaunchKernelGGL((average_kernel<3>), grid, dim3(256), 0, c->side, a);
-        else hipLaunchKernelGGL((average_kernel<0>), grid, dim3(256), 0, c->side, a);
-    } else if (split == 2) {
-        if (nt) hipLaunchKernelGGL((average_split_kernel<2, 3>), grid, dim3(256), 0, c->side, a);
-        else hipLaunchKernelGGL((average_split_kernel<2, 0>), grid, dim3(256), 0, c->side, a);
-    } else {
-        if (nt) hipLaunchKernelGGL((average_split_kernel<4, 3>), grid, dim3(256), 0, c->side, a);
-        else hipLaunchKernelGGL((average_split_kernel<4, 0>), grid, dim3(256), 0, c->side, a);
-    }
-    hipError_t e = hipGetLastError();
+    const bool ext = elastic || mask != c->all;
+    hipError_t e = ext ? launch_average<true>(a, grid, c->side, split, nt) : launch_average<false>(a, grid, c->side, split, nt);
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "average launch failed: %s", hipGetErrorString(e));
     return LASGD_OK;
 }
@@ -317,6 +361,7 @@ lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out)
         if (off > kMaxNpad) { delete c; return fail(nullptr, LASGD_ERR_UNSUPPORTED, "more than %llu elements per replica", (unsigned long long)kMaxNpad); }
     }
     c->npad = off;
+    c->all = c->K == 64 ? ~0ull : ((1ull << c->K) - 1ull);
     c->ntotal = total;
     c->bound.assign((size_t)c->K, 0);
     c->h_xptr.assign((size_t)c->K * c->n_tensors, nullptr);
@@ -390,49 +435,167 @@ lasgd_status lasgd_init_master(lasgd_ctx *c)
     if (!c) return LASGD_ERR_INVALID;
     if (c->storage != LASGD_BF16) return fail(c, LASGD_ERR_STATE, "storage is fp32: there is no master copy");
     if (c->n_bound != c->K) return fail(c, LASGD_ERR_STATE, "%d of %d replicas are bound", c->n_bound, c->K);
-    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "an average is in flight");
+    if (c->pending_mask) return fail(c, LASGD_ERR_STATE, "an average is in flight");
     lasgd_status st = enqueue_apply(c, OP_INIT, 0.f, 0);
     if (st != LASGD_OK) return st;
     c->master_ready = true;
-    c->snap_valid = false;
+    c->snap_mask = 0;
+    return LASGD_OK;
+}
+
+// ---- shared by the plain and the extended entry points -------------------
+// The plain calls are the extended ones with every replica taking part, one
+// step size and alpha = 1; they launch the lean kernels.
+
+static lasgd_status check_mask(lasgd_ctx *c, uint64_t mask, bool may_be_empty, const char *what)
+{
+    if (mask & ~c->all) return fail(c, LASGD_ERR_INVALID, "%s names replicas beyond K = %d", what, c->K);
+    if (!may_be_empty && !mask) return fail(c, LASGD_ERR_INVALID, "%s is empty", what);
+    return LASGD_OK;
+}
+
+static lasgd_status check_lrs(lasgd_ctx *c, const float *lr, uint64_t mask)
+{
+    if (!lr) return fail(c, LASGD_ERR_INVALID, "NULL learning-rate array");
+    for (int k = 0; k < c->K; ++k)
+        if (((mask >> k) & 1ull) && !std::isfinite(lr[k])) return fail(c, LASGD_ERR_INVALID, "learning rate of replica %d is not finite", k);
+    return LASGD_OK;
+}
+
+static bool fill_ext(const lasgd_ctx *c, ExtArgs &x, const float *lr, uint64_t step_mask, uint64_t merge_mask)
+{
+    x.step_mask = step_mask;
+    x.merge_mask = merge_mask;
+    x.alpha = c->alpha;
+    bool uniform = true;
+    float first = 0.f;
+    bool have = false;
+    for (int k = 0; k < 64; ++k) {
+        const bool in = k < c->K && ((step_mask >> k) & 1ull) && lr;
+        x.neg_lr_k[k] = in ? -lr[k] : 0.f;
+        if (in) {
+            if (!have) { first = lr[k]; have = true; }
+            else if (lr[k] != first) uniform = false;
+        }
+    }
+    return uniform;
+}
+
+static lasgd_status do_local_step(lasgd_ctx *c, const float *lr_k, float lr, uint64_t mask)
+{
+    lasgd_status st = check_ready_to_step(c, lr_k ? 0.f : lr);
+    if (st != LASGD_OK) return st;
+    if (!lr_k && mask == c->all) return enqueue_apply(c, OP_STEP, lr, 0);
+    if ((st = check_mask(c, mask, true, "mask")) != LASGD_OK) return st;
+    if ((st = check_lrs(c, lr_k, mask)) != LASGD_OK) return st;
+    if (!mask) return LASGD_OK;                        // nobody steps: nothing to enqueue
+    ExtArgs x{};
+    const bool uniform = fill_ext(c, x, lr_k, mask, 0);
+    if (uniform && mask == c->all) return enqueue_apply(c, OP_STEP, lr_k[0], 0);
+    return enqueue_apply(c, OP_STEP, 0.f, 0, &x);
+}
+
+static lasgd_status do_snapshot(lasgd_ctx *c, uint64_t mask)
+{
+    lasgd_status st = check_ready_to_step(c, 0.f);
+    if (st != LASGD_OK) return st;
+    if ((st = check_mask(c, mask, false, "mask")) != LASGD_OK) return st;
+    if (mask & c->pending_mask)
+        return fail(c, LASGD_ERR_STATE, "an average over some of these replicas is in flight and not merged: s may still be read");
+    if (mask == c->all) st = enqueue_apply(c, OP_SNAPSHOT, 0.f, 0);
+    else {
+        ExtArgs x{};
+        fill_ext(c, x, nullptr, mask, 0);
+        st = enqueue_apply(c, OP_SNAPSHOT, 0.f, 0, &x);
+    }
+    if (st != LASGD_OK) return st;
+    c->snap_mask |= mask;
+    return LASGD_OK;
+}
+
+static lasgd_status do_average(lasgd_ctx *c, uint64_t mask)
+{
+    lasgd_status st = check_mask(c, mask, false, "mask");
+    if (st != LASGD_OK) return st;
+    if (c->pending_mask) return fail(c, LASGD_ERR_STATE, "the previous average has not been merged by all its participants");
+    if (mask & ~c->snap_mask) return fail(c, LASGD_ERR_STATE, "no snapshot to average for some of these replicas");
+    if (c->side != c->main) {
+        LASGD_HIP(c, hipEventRecord(c->evA, c->main));
+        LASGD_HIP(c, hipStreamWaitEvent(c->side, c->evA, 0));
+    }
+    // the first mean initialises the centre: there is no earlier z to blend with
+    const bool elastic = c->beta != 1.f && c->center_valid;
+    st = enqueue_average(c, mask, elastic);
+    if (st != LASGD_OK) return st;
+    LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
+    c->pending_mask = mask;
+    c->avg_ever = true;
+    c->center_valid = true;
+    return LASGD_OK;
+}
+
+static lasgd_status do_merge(lasgd_ctx *c, int op, const float *lr_k, float lr, uint64_t step_mask,
+                             uint64_t merge_mask, int32_t resnapshot)
+{
+    lasgd_status st = check_ready_to_step(c, lr_k ? 0.f : lr);
+    if (st != LASGD_OK) return st;
+    if ((st = check_mask(c, merge_mask, false, "merge mask")) != LASGD_OK) return st;
+    if ((st = check_mask(c, step_mask, true, "step mask")) != LASGD_OK) return st;
+    if (op == OP_STEP_MERGE && lr_k && (st = check_lrs(c, lr_k, step_mask)) != LASGD_OK) return st;
+    if (!c->pending_mask) return fail(c, LASGD_ERR_STATE, "no average launched since the last merge");
+    if (merge_mask & ~c->pending_mask)
+        return fail(c, LASGD_ERR_STATE, "some of these replicas did not take part in the pending average or have merged already");
+    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    ExtArgs x{};
+    float same[64];
+    for (int k = 0; k < 64; ++k) same[k] = lr;
+    const bool uniform = fill_ext(c, x, lr_k ? lr_k : same, step_mask, merge_mask);
+    const bool plain = merge_mask == c->all && c->alpha == 1.f &&
+                       (op == OP_MERGE || (step_mask == c->all && uniform));
+    if (plain) st = enqueue_apply(c, op, lr_k ? lr_k[0] : lr, resnapshot ? 1 : 0);
+    else st = enqueue_apply(c, op, 0.f, resnapshot ? 1 : 0, &x);
+    if (st != LASGD_OK) return st;
+    c->pending_mask &= ~merge_mask;
+    if (resnapshot) c->snap_mask |= merge_mask;
+    else c->snap_mask &= ~merge_mask;
     return LASGD_OK;
 }
 
 lasgd_status lasgd_local_step(lasgd_ctx *c, float lr)
 {
     if (!c) return LASGD_ERR_INVALID;
-    lasgd_status st = check_ready_to_step(c, lr);
-    if (st != LASGD_OK) return st;
-    return enqueue_apply(c, OP_STEP, lr, 0);
+    return do_local_step(c, nullptr, lr, c->all);
+}
+
+lasgd_status lasgd_local_step_ex(lasgd_ctx *c, const float *lr, uint64_t mask)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!lr) return fail(c, LASGD_ERR_INVALID, "NULL learning-rate array");
+    return do_local_step(c, lr, 0.f, mask);
 }
 
 lasgd_status lasgd_snapshot(lasgd_ctx *c)
 {
     if (!c) return LASGD_ERR_INVALID;
-    lasgd_status st = check_ready_to_step(c, 0.f);
-    if (st != LASGD_OK) return st;
-    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "an average is in flight and not merged: s may still be read");
-    st = enqueue_apply(c, OP_SNAPSHOT, 0.f, 0);
-    if (st != LASGD_OK) return st;
-    c->snap_valid = true;
-    return LASGD_OK;
+    return do_snapshot(c, c->all);
+}
+
+lasgd_status lasgd_snapshot_ex(lasgd_ctx *c, uint64_t mask)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    return do_snapshot(c, mask);
 }
 
 lasgd_status lasgd_average(lasgd_ctx *c)
 {
     if (!c) return LASGD_ERR_INVALID;
-    if (c->avg_pending) return fail(c, LASGD_ERR_STATE, "the previous average has not been merged");
-    if (!c->snap_valid) return fail(c, LASGD_ERR_STATE, "no snapshot to average");
-    if (c->side != c->main) {
-        LASGD_HIP(c, hipEventRecord(c->evA, c->main));
-        LASGD_HIP(c, hipStreamWaitEvent(c->side, c->evA, 0));
-    }
-    lasgd_status st = enqueue_average(c);
-    if (st != LASGD_OK) return st;
-    LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
-    c->avg_pending = true;
-    c->avg_ever = true;
-    return LASGD_OK;
+    return do_average(c, c->all);
+}
+
+lasgd_status lasgd_average_ex(lasgd_ctx *c, uint64_t mask)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    return do_average(c, mask);
 }
 
 lasgd_status lasgd_average_done(lasgd_ctx *c, int32_t *done)
@@ -447,29 +610,57 @@ lasgd_status lasgd_average_done(lasgd_ctx *c, int32_t *done)
     return LASGD_OK;
 }
 
-static lasgd_status merge_common(lasgd_ctx *c, int op, float lr, int32_t resnapshot)
-{
-    lasgd_status st = check_ready_to_step(c, lr);
-    if (st != LASGD_OK) return st;
-    if (!c->avg_pending) return fail(c, LASGD_ERR_STATE, "no average launched since the last merge");
-    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
-    st = enqueue_apply(c, op, lr, resnapshot ? 1 : 0);
-    if (st != LASGD_OK) return st;
-    c->avg_pending = false;
-    c->snap_valid = resnapshot != 0;
-    return LASGD_OK;
-}
-
 lasgd_status lasgd_merge(lasgd_ctx *c, int32_t resnapshot)
 {
     if (!c) return LASGD_ERR_INVALID;
-    return merge_common(c, OP_MERGE, 0.f, resnapshot);
+    return do_merge(c, OP_MERGE, nullptr, 0.f, 0, c->all, resnapshot);
+}
+
+lasgd_status lasgd_merge_ex(lasgd_ctx *c, uint64_t mask, int32_t resnapshot)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    return do_merge(c, OP_MERGE, nullptr, 0.f, 0, mask, resnapshot);
 }
 
 lasgd_status lasgd_step_merge(lasgd_ctx *c, float lr, int32_t resnapshot)
 {
     if (!c) return LASGD_ERR_INVALID;
-    return merge_common(c, OP_STEP_MERGE, lr, resnapshot);
+    return do_merge(c, OP_STEP_MERGE, nullptr, lr, c->all, c->all, resnapshot);
+}
+
+lasgd_status lasgd_step_merge_ex(lasgd_ctx *c, const float *lr, uint64_t step_mask, uint64_t merge_mask,
+                                 int32_t resnapshot)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!lr) return fail(c, LASGD_ERR_INVALID, "NULL learning-rate array");
+    return do_merge(c, OP_STEP_MERGE, lr, 0.f, step_mask, merge_mask, resnapshot);
+}
+
+lasgd_status lasgd_set_elastic(lasgd_ctx *c, float alpha, float beta)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    if (!(alpha >= 0.f && alpha <= 1.f) || !(beta >= 0.f && beta <= 1.f))
+        return fail(c, LASGD_ERR_INVALID, "alpha and beta must lie in [0, 1]");
+    c->alpha = alpha;
+    c->beta = beta;
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_sgd_ar_step(lasgd_ctx *c, float lr)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    lasgd_status st = check_ready_to_step(c, lr);
+    if (st != LASGD_OK) return st;
+    ApplyArgs a{};
+    fill_common(c, a);
+    a.neg_lr = -lr;
+    uint64_t blocks = ((uint64_t)a.ntiles + 3) / 4;
+    if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
+    const dim3 grid((uint32_t)blocks);
+    hipError_t e = c->storage == LASGD_BF16 ? launch_sgd_ar<true>(a, grid, c->main, c->tune.vec, c->tune.nontemporal)
+                                            : launch_sgd_ar<false>(a, grid, c->main, c->tune.vec, c->tune.nontemporal);
+    if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return LASGD_OK;
 }
 
 lasgd_status lasgd_sync(lasgd_ctx *c)

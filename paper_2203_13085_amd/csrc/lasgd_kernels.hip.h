@@ -51,6 +51,16 @@ struct ApplyArgs {
     uint32_t tail_chunk;    // its length (>= 1 even when unused)
 };
 
+// What the extended entry points add: replicas that sit a call out, a step size
+// per replica (eta is indexed by each node's own clock, Algorithm 1) and the
+// elastic coefficient alpha of Sec. 3, Eq. 6.
+struct ExtArgs {
+    uint64_t step_mask;     // bit k: replica k takes the local update (or is snapshotted / initialised)
+    uint64_t merge_mask;    // bit k: replica k takes the global update
+    float alpha;            // 1 = step 9a of Algorithm 1 exactly
+    float neg_lr_k[64];     // -eta per replica
+};
+
 // ---- 128-bit / 64-bit accesses, optionally with the streaming hint --------
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
@@ -133,6 +143,15 @@ __device__ __forceinline__ float merge_elem(float x, float s, float z)
     return z + progress;
 }
 
+// Elastic form (Eq. 6 in the asynchronous setting): the pull alpha*(z - s) is
+// measured at the sent model and applied to the current one.  alpha == 1 keeps
+// the printed form of step 9a, so both entry-point families agree bit for bit there.
+__device__ __forceinline__ float merge_elem_elastic(float x, float s, float z, float alpha)
+{
+    float pulled = __builtin_fmaf(alpha, z - s, x);
+    return alpha == 1.0f ? merge_elem(x, s, z) : pulled;
+}
+
 #define LASGD_FOR4(body)                                                                       \
     {                                                                                          \
         { constexpr int c = 0; body }                                                          \
@@ -153,10 +172,10 @@ __device__ __forceinline__ float compv(const float4 &a, int c)
 // of full 256-element rows (VEC on the fast path); `count` bounds the ragged
 // path.  x/g point at the tile's first element in the caller's buffers
 // (storage dtype), xm/v/s at the tile's first element in the arenas.
-template <int VEC, int OP, bool BF16, int NT, bool FULL>
+template <int VEC, int OP, bool BF16, int NT, bool FULL, bool EXT>
 __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const void *gu, float *xm,
                                            float *v, float *s, const float4 (&zt)[VEC], float wd,
-                                           uint32_t count, uint32_t lane)
+                                           uint32_t count, uint32_t lane, float neg_lr, float alpha)
 {
     constexpr bool NEED_G = (OP == OP_STEP || OP == OP_STEP_MERGE);
     constexpr bool NEED_V = NEED_G;
@@ -187,9 +206,13 @@ __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const v
             const uint32_t e = j * 256u + lane * 4u;
             if constexpr (NEED_G)
                 LASGD_FOR4(step_elem(comp(x[j], c), comp(vv[j], c), compv(g[j], c), wd, a.mu,
-                                     a.neg_lr, a.nesterov);)
-            if constexpr (NEED_S)
-                LASGD_FOR4(comp(x[j], c) = merge_elem(compv(x[j], c), compv(ss[j], c), compv(zt[j], c));)
+                                     neg_lr, a.nesterov);)
+            if constexpr (NEED_S) {
+                if constexpr (EXT)
+                    LASGD_FOR4(comp(x[j], c) = merge_elem_elastic(compv(x[j], c), compv(ss[j], c), compv(zt[j], c), alpha);)
+                else
+                    LASGD_FOR4(comp(x[j], c) = merge_elem(compv(x[j], c), compv(ss[j], c), compv(zt[j], c));)
+            }
             if constexpr (OP == OP_INIT) vv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
             if constexpr (WRITE_V) st4<NT>(v + e, vv[j]);
             if constexpr (WRITE_X) {
@@ -214,8 +237,10 @@ __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const v
                 if constexpr (OP == OP_INIT) xe = bf16_widen(x16[e]);
                 if constexpr (NEED_V) ve = v[e];
                 if constexpr (NEED_S) se = s[e];
-                if constexpr (NEED_G) step_elem(xe, ve, ge, wd, a.mu, a.neg_lr, a.nesterov);
-                if constexpr (NEED_S) xe = merge_elem(xe, se, compv(zt[j], (int)i));
+                if constexpr (NEED_G) step_elem(xe, ve, ge, wd, a.mu, neg_lr, a.nesterov);
+                if constexpr (NEED_S)
+                    xe = EXT ? merge_elem_elastic(xe, se, compv(zt[j], (int)i), alpha)
+                             : merge_elem(xe, se, compv(zt[j], (int)i));
                 if constexpr (WRITE_V) v[e] = ve;
                 if constexpr (WRITE_X) {
                     xf[e] = xe;
@@ -229,8 +254,8 @@ __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const v
 
 // Multi-tensor apply.  Work item = (tile, group of kper replicas); one wave
 // per item, items strided over the grid.  All table reads are wave-uniform.
-template <int VEC, int OP, bool BF16, int NT>
-__global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
+template <int VEC, int OP, bool BF16, int NT, bool EXT>
+__device__ __forceinline__ void apply_body(const ApplyArgs &a, const ExtArgs *xa)
 {
     constexpr bool NEED_Z = (OP == OP_MERGE || OP == OP_STEP_MERGE);
     const uint32_t lane = threadIdx.x & 63u;
@@ -284,35 +309,89 @@ __global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
                 gu = static_cast<const char *>(a.gptr[pi]) + t.toff * esz;
             const size_t ao = (size_t)k * a.npad + t.aoff;
             float *xm = BF16 ? a.x32 + ao : nullptr;
-            if (full)
-                apply_tile<VEC, OP, BF16, NT, true>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane);
-            else
-                apply_tile<VEC, OP, BF16, NT, false>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane);
+#define LASGD_TILE(OPX, NLR, AL)                                                                             \
+    do {                                                                                                     \
+        if (full) apply_tile<VEC, OPX, BF16, NT, true, EXT>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane, NLR, AL); \
+        else apply_tile<VEC, OPX, BF16, NT, false, EXT>(a, xu, gu, xm, a.v + ao, a.s + ao, zt, t.wd, t.count, lane, NLR, AL);     \
+    } while (0)
+            if constexpr (!EXT) {
+                LASGD_TILE(OP, a.neg_lr, 1.0f);
+            } else {
+                // a replica may take the local update, the global update, both or neither
+                const bool in_step = (xa->step_mask >> k) & 1ull;
+                const bool in_merge = (xa->merge_mask >> k) & 1ull;
+                const float nlr = xa->neg_lr_k[k];
+                if constexpr (OP == OP_STEP_MERGE) {
+                    if (in_step && in_merge) LASGD_TILE(OP_STEP_MERGE, nlr, xa->alpha);
+                    else if (in_step) LASGD_TILE(OP_STEP, nlr, 1.0f);
+                    else if (in_merge) LASGD_TILE(OP_MERGE, 0.0f, xa->alpha);
+                } else if constexpr (OP == OP_MERGE) {
+                    if (in_merge) LASGD_TILE(OP_MERGE, 0.0f, xa->alpha);
+                } else {
+                    if (in_step) LASGD_TILE(OP, nlr, 1.0f);
+                }
+            }
+#undef LASGD_TILE
         }
     }
+}
+
+template <int VEC, int OP, bool BF16, int NT>
+__global__ __launch_bounds__(256) void apply_kernel(const ApplyArgs a)
+{
+    apply_body<VEC, OP, BF16, NT, false>(a, nullptr);
+}
+
+template <int VEC, int OP, bool BF16, int NT>
+__global__ __launch_bounds__(256) void apply_ext_kernel(const ApplyArgs a, const ExtArgs xa)
+{
+    apply_body<VEC, OP, BF16, NT, true>(a, &xa);
 }
 
 // ---- the mean (Sec. 3, Eq. 8) -----------------------------------------------
 // z[e] = (1/K) sum_k s[k][e], fp64 accumulation in replica order, one rounding.
 // The arenas are contiguous and padded with zeros, so this is a flat pass.
+// EXT variants: the mean runs over a list of participants (partial All-Reduce,
+// Sec. 6; the divisor is their number) and may be blended into the previous
+// centre, z = (1-beta) z + beta mean (Sec. 3, Eq. 5).
 struct AvgArgs {
     const float *s;
     float *z;
     uint64_t npad;      // elements per replica, multiple of 4
     uint64_t nvec;      // npad / 4
-    uint32_t K;
+    uint32_t K;         // replicas summed (participants in the EXT variants)
     int32_t use_mul;    // K is a power of two: multiply by the exact reciprocal
     double inv_k, k_as_double;
+    int32_t elastic;    // EXT: blend with the previous centre
+    double beta, one_minus_beta;
+    uint8_t idx[64];    // EXT: the participants, ascending
 };
 
-__device__ __forceinline__ float finish_mean(double acc, const AvgArgs &a)
+template <bool EXT> __device__ __forceinline__ uint32_t replica_of(const AvgArgs &a, uint32_t j)
 {
-    return a.use_mul ? (float)(acc * a.inv_k) : (float)(acc / a.k_as_double);
+    if constexpr (EXT) return a.idx[j];
+    else return j;
 }
+
+template <bool EXT> __device__ __forceinline__ float finish_mean(double acc, float z_old, const AvgArgs &a)
+{
+    const double mean = a.use_mul ? acc * a.inv_k : acc / a.k_as_double;
+    if constexpr (EXT) {
+        if (a.elastic) {
+            const double keep = a.one_minus_beta * (double)z_old;
+            const double pull = a.beta * mean;
+            return (float)(keep + pull);
+        }
+    }
+    return (float)mean;
+}
+
+#define LASGD_ACC4(r)                                                                          \
+    do { a0 += (double)(r).x; a1 += (double)(r).y; a2 += (double)(r).z; a3 += (double)(r).w; } while (0)
 
 // SPLIT == 1: every lane owns one 128-bit column and walks all K replicas,
 // eight loads in flight at a time.
-template <int NT>
+template <int NT, bool EXT>
 __global__ __launch_bounds__(256) void average_kernel(const AvgArgs a)
 {
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
@@ -323,27 +402,28 @@ __global__ __launch_bounds__(256) void average_kernel(const AvgArgs a)
         for (; k + 8u <= a.K; k += 8u) {
             float4 r[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+            for (int u = 0; u < 8; ++u) r[u] = ld4<NT>(p + (uint64_t)replica_of<EXT>(a, k + u) * a.npad);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
-            }
+            for (int u = 0; u < 8; ++u) LASGD_ACC4(r[u]);
         }
         if (k + 4u <= a.K) {
             float4 r[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+            for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)replica_of<EXT>(a, k + u) * a.npad);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
-            }
+            for (int u = 0; u < 4; ++u) LASGD_ACC4(r[u]);
             k += 4u;
         }
         for (; k < a.K; ++k) {
-            float4 r = ld4<NT>(p + (uint64_t)k * a.npad);
-            a0 += (double)r.x; a1 += (double)r.y; a2 += (double)r.z; a3 += (double)r.w;
+            float4 r = ld4<NT>(p + (uint64_t)replica_of<EXT>(a, k) * a.npad);
+            LASGD_ACC4(r);
         }
-        float4 out = make_float4(finish_mean(a0, a), finish_mean(a1, a), finish_mean(a2, a), finish_mean(a3, a));
+        float4 zo = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (EXT) {
+            if (a.elastic) zo = *reinterpret_cast<const float4 *>(a.z + i * 4u);
+        }
+        float4 out = make_float4(finish_mean<EXT>(a0, zo.x, a), finish_mean<EXT>(a1, zo.y, a),
+                                 finish_mean<EXT>(a2, zo.z, a), finish_mean<EXT>(a3, zo.w, a));
         st4<NT>(a.z + i * 4u, out);
     }
 }
@@ -353,7 +433,7 @@ __global__ __launch_bounds__(256) void average_kernel(const AvgArgs a)
 // in fp64, the partial sums meet in LDS and are added in group order.  More
 // independent load streams per column for large K; the result can differ from
 // the in-order sum only by fp64 rounding, i.e. in fp32 only at double-rounding ties.
-template <int SPLIT, int NT>
+template <int SPLIT, int NT, bool EXT>
 __global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
 {
     constexpr uint32_t COLS = 256u / SPLIT;             // 128-bit columns per workgroup pass
@@ -372,15 +452,13 @@ __global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
             for (; k + 4u <= ke; k += 4u) {
                 float4 r[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)(k + u) * a.npad);
+                for (int u = 0; u < 4; ++u) r[u] = ld4<NT>(p + (uint64_t)replica_of<EXT>(a, k + u) * a.npad);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    a0 += (double)r[u].x; a1 += (double)r[u].y; a2 += (double)r[u].z; a3 += (double)r[u].w;
-                }
+                for (int u = 0; u < 4; ++u) LASGD_ACC4(r[u]);
             }
             for (; k < ke; ++k) {
-                float4 r = ld4<NT>(p + (uint64_t)k * a.npad);
-                a0 += (double)r.x; a1 += (double)r.y; a2 += (double)r.z; a3 += (double)r.w;
+                float4 r = ld4<NT>(p + (uint64_t)replica_of<EXT>(a, k) * a.npad);
+                LASGD_ACC4(r);
             }
         }
         part[g][c][0] = a0; part[g][c][1] = a1; part[g][c][2] = a2; part[g][c][3] = a3;
@@ -388,6 +466,8 @@ __global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
         // 256 threads finish COLS*4 = 1024/SPLIT elements: 4/SPLIT each, consecutive
         constexpr uint32_t PER = 4u / SPLIT;             // 2 or 1
         const uint32_t e0 = threadIdx.x * PER;           // element within the tile
+        const uint64_t ebase = tile * COLS * 4u + e0;
+        const bool inside = ebase + PER <= a.npad;
         float outv[PER];
 #pragma unroll
         for (uint32_t q = 0; q < PER; ++q) {
@@ -395,14 +475,80 @@ __global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
             double acc = 0.0;
 #pragma unroll
             for (int gg = 0; gg < SPLIT; ++gg) acc += part[gg][e >> 2][e & 3u];
-            outv[q] = finish_mean(acc, a);
+            float zo = 0.f;
+            if constexpr (EXT) {
+                if (a.elastic && inside) zo = a.z[ebase + q];
+            }
+            outv[q] = finish_mean<EXT>(acc, zo, a);
         }
-        const uint64_t ebase = tile * COLS * 4u + e0;
-        if (ebase + PER <= a.npad) {
+        if (inside) {
             if constexpr (PER == 2) *reinterpret_cast<float2 *>(a.z + ebase) = make_float2(outv[0], outv[PER - 1]);
             else a.z[ebase] = outv[0];
         }
         __syncthreads();
+    }
+}
+
+// ---- SGD All-Reduce comparator (Sec. 2; "SGD-AR" of Table 1) -----------------
+// One wave per tile: the K gradients of the tile are averaged (fp64 in replica
+// order, one rounding to fp32) and every replica takes the local update with
+// that mean gradient.  Same 20 bytes per replica-parameter as a local step.
+template <int VEC, bool BF16, int NT>
+__global__ __launch_bounds__(256) void sgd_ar_kernel(const ApplyArgs a)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * 4u;
+    constexpr size_t ESZ = BF16 ? 2 : 4;
+    for (uint32_t tile = wave0; tile < a.ntiles; tile += nwaves) {
+        const Tile t = a.tiles[tile];
+#pragma unroll 1
+        for (int j = 0; j < VEC; ++j) {                   // one 256-element row of the tile at a time
+        const uint32_t e0 = j * 256u + lane * 4u;
+        const uint32_t n = (e0 >= t.count) ? 0u : (t.count - e0 < 4u) ? t.count - e0 : 4u;
+        const bool vec_ok = (n == 4u);
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        for (uint32_t k = 0; k < a.K; ++k) {
+            const char *gu = static_cast<const char *>(a.gptr[(size_t)k * a.n_tensors + t.tensor]) + t.toff * ESZ;
+            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (vec_ok) {
+                r = BF16 ? widen4(ld2<NT>(reinterpret_cast<const uint16_t *>(gu) + e0))
+                         : ld4<NT>(reinterpret_cast<const float *>(gu) + e0);
+            } else {
+                for (uint32_t i = 0; i < n; ++i) {
+                    const float ge = BF16 ? bf16_widen(reinterpret_cast<const uint16_t *>(gu)[e0 + i])
+                                          : reinterpret_cast<const float *>(gu)[e0 + i];
+                    if (i == 0) r.x = ge; else if (i == 1) r.y = ge; else r.z = ge;
+                }
+            }
+            LASGD_ACC4(r);
+        }
+        const double kd = (double)a.K;
+        const float4 gbar = make_float4((float)(a0 / kd), (float)(a1 / kd), (float)(a2 / kd), (float)(a3 / kd));
+        for (uint32_t k = 0; k < a.K; ++k) {
+            const size_t pi = (size_t)k * a.n_tensors + t.tensor;
+            char *xu = static_cast<char *>(a.xptr[pi]) + t.toff * ESZ;
+            const size_t ao = (size_t)k * a.npad + t.aoff;
+            float *xf = BF16 ? a.x32 + ao : reinterpret_cast<float *>(xu);
+            uint16_t *x16 = reinterpret_cast<uint16_t *>(xu);
+            float *v = a.v + ao;
+            if (vec_ok) {
+                float4 x = ld4<NT>(xf + e0), vv = ld4<NT>(v + e0);
+                LASGD_FOR4(step_elem(comp(x, c), comp(vv, c), compv(gbar, c), t.wd, a.mu, a.neg_lr, a.nesterov);)
+                st4<NT>(v + e0, vv);
+                st4<NT>(xf + e0, x);
+                if constexpr (BF16) st2<NT>(x16 + e0, round4(x));
+            } else {
+                for (uint32_t i = 0; i < n; ++i) {
+                    float xe = xf[e0 + i], ve = v[e0 + i];
+                    step_elem(xe, ve, compv(gbar, (int)i), t.wd, a.mu, a.neg_lr, a.nesterov);
+                    v[e0 + i] = ve;
+                    xf[e0 + i] = xe;
+                    if constexpr (BF16) x16[e0 + i] = (uint16_t)bf16_round(xe);
+                }
+            }
+        }
+        }
     }
 }
 
