@@ -71,6 +71,103 @@ def cpu_baseline(w, seconds: float = 12.0) -> dict:
             "ms_per_cycle": 1e3 * dt / n}
 
 
+def run_variant(args, w, make, alg) -> dict:
+    """Timed loops over the extended entry points; one JSON line in the same format.
+    Bytes are algorithmic: 20 B per replica-parameter that steps, +8 B (+4/K for z) per
+    replica-parameter that merges and re-sends, 4(P+1) B per parameter for a mean over P."""
+    import numpy as np
+    import torch
+    K, N = w.K, w.N
+    full = (1 << K) - 1
+    dev = make(side=True)
+    c = dev.ctx
+    per_rp_step = alg["local_step"] / (K * N)
+    steps_done = 0          # replica-steps, for params/s
+    nbytes = 0.0
+
+    if args.mode == "sgd_ar":
+        def one():
+            nonlocal steps_done, nbytes
+            c.sgd_ar_step(w.lr)
+            steps_done += K
+            nbytes += alg["local_step"]
+        what = "one lasgd_sgd_ar_step: mean of the K gradients + the same local update on all K replicas"
+    else:
+        if args.mode == "elastic":
+            c.set_elastic(0.5, 0.5)
+        dev.prologue(w.lr)
+        rng = np.random.default_rng(0)
+        p = np.array([11.2, 72.8, 11.1, 0.2, 0.6, 3.9])
+        rot = [0]
+
+        def one():
+            nonlocal steps_done, nbytes
+            if args.mode == "dynamic":
+                # steps per All-Reduce from the paper's histogram (tau_max = 5), slower nodes take fewer
+                base = min(int(rng.choice(6, p=p / p.sum())) + 1, 5)
+                counts = [max(1, base - (k % 3 == 0)) for k in range(K)]
+                for j in range(max(counts)):
+                    mask = sum(1 << k for k in range(K) if counts[k] > j)
+                    lrs = [w.lr] * K
+                    act = bin(mask).count("1")
+                    if j == max(counts) - 1:
+                        c.step_merge_ex(lrs, mask, full, True)
+                        c.average()
+                        nbytes += act * N * per_rp_step + 8 * K * N + 4 * N + alg["average"]
+                    else:
+                        c.local_step_ex(lrs, mask)
+                        nbytes += act * N * per_rp_step
+                    steps_done += act
+            elif args.mode == "partial":
+                # three quarters of the replicas take part in each All-Reduce, rotating
+                P = max(1, (3 * K) // 4)
+                part = sum(1 << ((rot[0] + i) % K) for i in range(P))
+                rot[0] += 1
+                late = part & ~one.prev
+                for _ in range(w.m - 1):
+                    c.local_step(w.lr)
+                c.step_merge_ex([w.lr] * K, full, one.prev, True)
+                if late:
+                    c.snapshot_ex(late)
+                c.average_ex(part)
+                one.prev = part
+                steps_done += K * w.m
+                nbytes += w.m * alg["local_step"] + bin(one.prev).count("1") * N * 8 + 4 * N + 4 * (P + 1) * N \
+                    + bin(late).count("1") * N * 8
+            else:   # elastic: the headline cycle with alpha = beta = 0.5
+                for _ in range(w.m - 1):
+                    c.local_step(w.lr)
+                c.step_merge(w.lr, True)
+                c.average()
+                steps_done += K * w.m
+                nbytes += (w.m - 1) * alg["local_step"] + alg["step_merge"] + alg["average"] + 4 * N
+        one.prev = full
+        what = {"dynamic": "one All-Reduce round: 1..5 masked local steps per replica (paper's histogram), fused step+merge, mean",
+                "partial": "one cycle with 3/4 of the replicas in each All-Reduce (rotating); latecomers re-send",
+                "elastic": "the headline cycle with alpha = beta = 0.5"}[args.mode]
+
+    for _ in range(args.warmup):
+        one()
+    c.sync(); torch.cuda.synchronize()
+    steps_done, nbytes = 0, 0.0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one()
+    c.sync(); torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tuning = c.get_tuning()
+    dev.close()
+    gbps = nbytes / dt / 1e9
+    return {"metric": "params/sec and HBM GB/s (% of peak) for fused LASGD step+merge, K replicas",
+            "value": steps_done * N / dt, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16 storage, f32 arithmetic" if w.storage == "bf16" else "f32", "data": "synthetic",
+            "config": {"workload": f"configs[{args.config}]: {w.name}, K={K}, {N} params/replica, mode={args.mode}",
+                       "step": what, "mode": args.mode, "tuning": tuning},
+            "roofline": {"bound": "hbm", "kernel": "whole step (all launches)", "achieved": gbps, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS, "traffic": None}}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +179,9 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three plain 1 GiB device copies first (a kernel of known traffic, "
                          "to calibrate profiler byte counters)")
+    ap.add_argument("--mode", default="lasgd", choices=["lasgd", "sgd_ar", "dynamic", "elastic", "partial"],
+                    help="lasgd: the headline cycle; the others time the extended entry points "
+                         "(SGD All-Reduce step, scripted adaptive cadence, alpha=beta=0.5, 75%% partial All-Reduce)")
     ap.add_argument("--tune", type=str, default="", help="k=v,k=v launch-shape knobs (lasgd_tuning fields)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -133,6 +233,9 @@ def main() -> int:
 
     alg = algorithmic_bytes(w.K, w.N, bf16)
     cycle_bytes = (w.m - 1) * alg["local_step"] + alg["step_merge"] + alg["average"]
+    if args.mode != "lasgd":
+        print(json.dumps(run_variant(args, w, make, alg)), flush=True)
+        return 0
 
     # ---------------- the timed region: whole cycles, overlapped mean ----------------
     dev = make(side=True)
