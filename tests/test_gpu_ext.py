@@ -222,3 +222,37 @@ def test_mask_order_rules():
         c.sync()
     finally:
         dev.close()
+
+
+@pytest.mark.parametrize("tau_max", [1, 3, 5])
+def test_live_polling_replayed_through_the_oracle(tau_max):
+    """The real adaptive rule: poll "All Reduce done" on the device, cap at
+    tau_max.  Which iterations fire depends on timing, so the decisions are
+    recorded and replayed through the oracle; whatever they were, the states
+    must agree, and no replica may take more than tau_max steps per All-Reduce."""
+    w = W.small(K=8, numels=(1 << 18, 4096, 100), T=24)
+    orc, dev, grads = _pair(w)
+    try:
+        g = grads(1)
+        dev.load_grads(g)              # one gradient set for every step: no host sync inside the loop
+        orc.prologue(g, w.lr)
+        dev.prologue(w.lr)
+        tau, fired_at, since = 0, [], 0
+        for i in range(1, w.T + 1):
+            tau, fired = dev.adaptive_iteration(w.lr, tau, tau_max)
+            since += 1
+            if fired:
+                fired_at.append(i)
+                assert since <= tau_max
+                since = 0
+        say(f"[live] tau_max={tau_max}: global updates fired at iterations {fired_at}")
+        if tau_max == 1:
+            assert fired_at == list(range(1, w.T + 1))
+        for i in range(1, w.T + 1):
+            orc.local_step(g, w.lr)
+            if i in fired_at:
+                orc.merge(True)
+                orc.average()
+        compare_state(dev, orc, w.T)
+    finally:
+        dev.close()
