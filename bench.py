@@ -329,15 +329,19 @@ def main() -> int:
         ser.ctx.sync(); torch.cuda.synchronize()
         ms_serial = 1e3 * (time.perf_counter() - t0) / ns
         ser.close()
-        # time the main stream lost waiting for the mean: what step_merge took in the
-        # pipelined run beyond what it takes alone
-        wait = max(0.0, kern_ms["step_merge"] - t_sm)
+        # time the main stream lost waiting for the mean: how long after the main stream
+        # was ready for a step_merge (event before it) the previous mean ended (event after
+        # it on the side stream); negative = the mean was done long before, no wait
+        gaps = [ev["step_merge"][i + 1][0].elapsed_time(ev["average"][i][1]) for i in range(len(ev["average"]) - 1)]
+        wait = float(np.mean([max(0.0, g) for g in gaps])) if gaps else 0.0
+        slack = float(np.mean(gaps)) if gaps else 0.0
         detail = {
             "alone_ms": {"local_step": t_step, "step_merge": t_sm, "average": t_av},
             "alone_GBps": {"local_step": alg["local_step"] / t_step / 1e6, "step_merge": alg["step_merge"] / t_sm / 1e6,
                            "average": alg["average"] / t_av / 1e6},
             "ms_per_cycle_one_stream": ms_serial,
-            "overlap": {"T_avg_alone_ms": t_av, "T_wait_ms": wait, "hidden_frac": 1.0 - min(1.0, wait / t_av),
+            "overlap": {"T_avg_alone_ms": t_av, "T_avg_overlapped_ms": kern_ms["average"], "T_wait_ms": wait,
+                        "mean_ended_before_merge_by_ms": -slack, "hidden_frac": 1.0 - min(1.0, wait / t_av),
                         "contention_cost": (ms_per_step - (ms_serial - t_av)) / t_av},
         }
     else:

@@ -93,6 +93,7 @@ typedef struct {
                               adjacent; <0 = whole replica after whole replica                       */
     int32_t chunk_merge;   /* same for merge / step_merge (a chunk's z tiles are reused K times within
                               a short window)                                                        */
+    int32_t waves_per_block; /* independent waves per workgroup in the multi-tensor kernels: 1, 2 or 4  */
 } lasgd_tuning;
 
 /*

@@ -48,7 +48,8 @@ class Tuning(ctypes.Structure):
     _fields_ = [("vec", ctypes.c_int32), ("kper_step", ctypes.c_int32), ("kper_merge", ctypes.c_int32),
                 ("max_blocks", ctypes.c_int32), ("avg_split", ctypes.c_int32),
                 ("avg_max_blocks", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
-                ("chunk_step", ctypes.c_int32), ("chunk_merge", ctypes.c_int32)]
+                ("chunk_step", ctypes.c_int32), ("chunk_merge", ctypes.c_int32),
+                ("waves_per_block", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None

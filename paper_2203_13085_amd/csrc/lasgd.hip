@@ -133,7 +133,9 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
 
 // Defaults from sweeps on MI355X over the five benchmark workloads: the finest
 // tile (one 128-bit vector per lane), one wave per (tile, replica), a grid that
-// covers all items, tiles of a replica adjacent in launch order, and the
+// covers all items in one-wave workgroups (the waves are independent, and
+// single-wave groups dispatch and retire with the least friction), tiles of a
+// replica adjacent in launch order, and the
 // streaming hint on every access except z once the state no longer fits the
 // 256 MB memory-side cache.  Items are ordered in chunks of 16384 tiles (16 MB
 // per array): long contiguous runs per replica, and the chunk's z is still
@@ -148,42 +150,43 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
     t.avg_split = c.K >= 8 ? 4 : 1;
     t.avg_max_blocks = -1;
     t.nontemporal = ((uint64_t)c.K * c.npad * sizeof(float) >= (128ull << 20)) ? 3 : 0;
+    t.waves_per_block = 1;
     t.chunk_step = 16384;
     t.chunk_merge = 16384;
     return t;
 }
 
 template <int VEC, int OP, bool BF16>
-hipError_t launch_nt(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int nt)
+hipError_t launch_nt(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, dim3 bs, hipStream_t st, int nt)
 {
     if (xa) {      // extended variants: hints all on or all off
-        if (nt & 3) hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 3>), grid, dim3(256), 0, st, a, *xa);
-        else hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 0>), grid, dim3(256), 0, st, a, *xa);
+        if (nt & 3) hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 3>), grid, bs, 0, st, a, *xa);
+        else hipLaunchKernelGGL((apply_ext_kernel<VEC, OP, BF16, 0>), grid, bs, 0, st, a, *xa);
         return hipGetLastError();
     }
     switch (nt & 3) {
-    case 0: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 0>), grid, dim3(256), 0, st, a); break;
-    case 1: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 1>), grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 2>), grid, dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 3>), grid, dim3(256), 0, st, a); break;
+    case 0: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 0>), grid, bs, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 1>), grid, bs, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 2>), grid, bs, 0, st, a); break;
+    default: hipLaunchKernelGGL((apply_kernel<VEC, OP, BF16, 3>), grid, bs, 0, st, a); break;
     }
     return hipGetLastError();
 }
 
 template <int OP, bool BF16>
-hipError_t launch_vec(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int vec, int nt)
+hipError_t launch_vec(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, dim3 bs, hipStream_t st, int vec, int nt)
 {
     switch (vec) {
-    case 1: return launch_nt<1, OP, BF16>(a, xa, grid, st, nt);
-    case 2: return launch_nt<2, OP, BF16>(a, xa, grid, st, nt);
-    default: return launch_nt<4, OP, BF16>(a, xa, grid, st, nt);
+    case 1: return launch_nt<1, OP, BF16>(a, xa, grid, bs, st, nt);
+    case 2: return launch_nt<2, OP, BF16>(a, xa, grid, bs, st, nt);
+    default: return launch_nt<4, OP, BF16>(a, xa, grid, bs, st, nt);
     }
 }
 
 template <int OP>
-hipError_t launch_op(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, hipStream_t st, int vec, int nt, bool bf16)
+hipError_t launch_op(const ApplyArgs &a, const ExtArgs *xa, dim3 grid, dim3 bs, hipStream_t st, int vec, int nt, bool bf16)
 {
-    return bf16 ? launch_vec<OP, true>(a, xa, grid, st, vec, nt) : launch_vec<OP, false>(a, xa, grid, st, vec, nt);
+    return bf16 ? launch_vec<OP, true>(a, xa, grid, bs, st, vec, nt) : launch_vec<OP, false>(a, xa, grid, bs, st, vec, nt);
 }
 
 void fill_common(const lasgd_ctx *c, ApplyArgs &a)
@@ -226,18 +229,19 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const Ext
     a.full_items = nfull * a.chunk * a.kgroups;
     a.tail_first = nfull * a.chunk;
     a.tail_chunk = a.ntiles - a.tail_first ? a.ntiles - a.tail_first : 1u;
-    uint64_t blocks = (nitems + 3) / 4;                     // four waves per workgroup
+    const uint32_t wpb = (uint32_t)c->tune.waves_per_block;
+    uint64_t blocks = (nitems + wpb - 1) / wpb;
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
-    const dim3 grid((uint32_t)blocks);
+    const dim3 grid((uint32_t)blocks), bs(64u * wpb);
     const bool bf16 = c->storage == LASGD_BF16;
     const int vec = c->tune.vec, nt = c->tune.nontemporal;
     hipError_t e = hipSuccess;
     switch (op) {
-    case OP_STEP: e = launch_op<OP_STEP>(a, xa, grid, c->main, vec, nt, bf16); break;
-    case OP_MERGE: e = launch_op<OP_MERGE>(a, xa, grid, c->main, vec, nt, bf16); break;
-    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, xa, grid, c->main, vec, nt, bf16); break;
-    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, xa, grid, c->main, vec, nt, bf16); break;
-    case OP_INIT: e = launch_vec<OP_INIT, true>(a, nullptr, grid, c->main, vec, nt); break;
+    case OP_STEP: e = launch_op<OP_STEP>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
+    case OP_MERGE: e = launch_op<OP_MERGE>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
+    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
+    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
+    case OP_INIT: e = launch_vec<OP_INIT, true>(a, nullptr, grid, bs, c->main, vec, nt); break;
     default: return fail(c, LASGD_ERR_INVALID, "unknown op %d", op);
     }
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
@@ -245,12 +249,12 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const Ext
 }
 
 template <bool BF16>
-hipError_t launch_sgd_ar(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec, int nt)
+hipError_t launch_sgd_ar(const ApplyArgs &a, dim3 grid, dim3 bs, hipStream_t st, int vec, int nt)
 {
 #define LASGD_AR(V)                                                                             \
     do {                                                                                        \
-        if (nt & 3) hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 3>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 0>), grid, dim3(256), 0, st, a);        \
+        if (nt & 3) hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 3>), grid, bs, 0, st, a); \
+        else hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 0>), grid, bs, 0, st, a);        \
     } while (0)
     if (vec == 1) LASGD_AR(1);
     else if (vec == 2) LASGD_AR(2);
@@ -260,11 +264,11 @@ hipError_t launch_sgd_ar(const ApplyArgs &a, dim3 grid, hipStream_t st, int vec,
 }
 
 template <bool EXT>
-hipError_t launch_average(const AvgArgs &a, dim3 grid, hipStream_t st, int split, bool nt)
+hipError_t launch_average(const AvgArgs &a, dim3 grid, hipStream_t st, int split, bool nt, uint32_t bs1)
 {
     if (split == 1) {
-        if (nt) hipLaunchKernelGGL((average_kernel<3, EXT>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((average_kernel<0, EXT>), grid, dim3(256), 0, st, a);
+        if (nt) hipLaunchKernelGGL((average_kernel<3, EXT>), grid, dim3(bs1), 0, st, a);
+        else hipLaunchKernelGGL((average_kernel<0, EXT>), grid, dim3(bs1), 0, st, a);
     } else if (split == 2) {
         if (nt) hipLaunchKernelGGL((average_split_kernel<2, 3, EXT>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((average_split_kernel<2, 0, EXT>), grid, dim3(256), 0, st, a);
@@ -294,14 +298,15 @@ lasgd_status enqueue_average(lasgd_ctx *c, uint64_t mask, bool elastic)
     a.beta = (double)c->beta;
     a.one_minus_beta = 1.0 - (double)c->beta;
     const int split = c->tune.avg_split;
-    const uint64_t cols = 256u / (uint32_t)split;
+    const uint32_t bs1 = 64u * (uint32_t)c->tune.waves_per_block;           // block size of the unsplit kernel
+    const uint64_t cols = split == 1 ? bs1 : 256u / (uint32_t)split;
     uint64_t blocks = (a.nvec + cols - 1) / cols;
     if (c->tune.avg_max_blocks > 0 && blocks > (uint64_t)c->tune.avg_max_blocks) blocks = (uint64_t)c->tune.avg_max_blocks;
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
     const dim3 grid((uint32_t)blocks);
     const bool nt = (c->tune.nontemporal & 1) != 0;
     const bool ext = elastic || mask != c->all;
-    hipError_t e = ext ? launch_average<true>(a, grid, c->side, split, nt) : launch_average<false>(a, grid, c->side, split, nt);
+    hipError_t e = ext ? launch_average<true>(a, grid, c->side, split, nt, bs1) : launch_average<false>(a, grid, c->side, split, nt, bs1);
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "average launch failed: %s", hipGetErrorString(e));
     return LASGD_OK;
 }
@@ -654,11 +659,12 @@ lasgd_status lasgd_sgd_ar_step(lasgd_ctx *c, float lr)
     ApplyArgs a{};
     fill_common(c, a);
     a.neg_lr = -lr;
-    uint64_t blocks = ((uint64_t)a.ntiles + 3) / 4;
+    const uint32_t wpb = (uint32_t)c->tune.waves_per_block;
+    uint64_t blocks = ((uint64_t)a.ntiles + wpb - 1) / wpb;
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
-    const dim3 grid((uint32_t)blocks);
-    hipError_t e = c->storage == LASGD_BF16 ? launch_sgd_ar<true>(a, grid, c->main, c->tune.vec, c->tune.nontemporal)
-                                            : launch_sgd_ar<false>(a, grid, c->main, c->tune.vec, c->tune.nontemporal);
+    const dim3 grid((uint32_t)blocks), bs(64u * wpb);
+    hipError_t e = c->storage == LASGD_BF16 ? launch_sgd_ar<true>(a, grid, bs, c->main, c->tune.vec, c->tune.nontemporal)
+                                            : launch_sgd_ar<false>(a, grid, bs, c->main, c->tune.vec, c->tune.nontemporal);
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return LASGD_OK;
 }
@@ -723,6 +729,11 @@ lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
     if (t->nontemporal) {
         if (t->nontemporal < 0 || t->nontemporal > 4) return fail(c, LASGD_ERR_INVALID, "nontemporal outside 0..4");
         n.nontemporal = t->nontemporal == 4 ? 0 : t->nontemporal;      // 4 = switch the hints off again
+    }
+    if (t->waves_per_block) {
+        if (t->waves_per_block != 1 && t->waves_per_block != 2 && t->waves_per_block != 4)
+            return fail(c, LASGD_ERR_INVALID, "waves_per_block must be 1, 2 or 4");
+        n.waves_per_block = t->waves_per_block;
     }
     if (t->chunk_step) n.chunk_step = t->chunk_step < 0 ? -1 : t->chunk_step;
     if (t->chunk_merge) n.chunk_merge = t->chunk_merge < 0 ? -1 : t->chunk_merge;

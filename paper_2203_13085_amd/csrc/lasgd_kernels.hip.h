@@ -254,13 +254,16 @@ __device__ __forceinline__ void apply_tile(const ApplyArgs &a, void *xu, const v
 
 // Multi-tensor apply.  Work item = (tile, group of kper replicas); one wave
 // per item, items strided over the grid.  All table reads are wave-uniform.
+// The waves of a workgroup are independent (no LDS, no barrier), so the
+// workgroup size (64, 128 or 256 threads) is purely a dispatch-granularity knob.
 template <int VEC, int OP, bool BF16, int NT, bool EXT>
 __device__ __forceinline__ void apply_body(const ApplyArgs &a, const ExtArgs *xa)
 {
     constexpr bool NEED_Z = (OP == OP_MERGE || OP == OP_STEP_MERGE);
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * 4u;
+    const uint32_t wpb = blockDim.x >> 6;                  // independent waves per workgroup
+    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * wpb;
     for (uint32_t item = wave0; item < a.nitems; item += nwaves) {
         // Item order: tiles are taken in chunks of a.chunk; inside a chunk the items run
         // replica group by replica group, so that each replica's arrays are swept in
@@ -394,8 +397,8 @@ template <bool EXT> __device__ __forceinline__ float finish_mean(double acc, flo
 template <int NT, bool EXT>
 __global__ __launch_bounds__(256) void average_kernel(const AvgArgs a)
 {
-    const uint64_t stride = (uint64_t)gridDim.x * 256u;
-    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < a.nvec; i += stride) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.nvec; i += stride) {
         const float *p = a.s + i * 4u;
         double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
         uint32_t k = 0;
@@ -497,8 +500,9 @@ template <int VEC, bool BF16, int NT>
 __global__ __launch_bounds__(256) void sgd_ar_kernel(const ApplyArgs a)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * 4u;
+    const uint32_t wpb = blockDim.x >> 6;
+    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));
+    const uint32_t nwaves = gridDim.x * wpb;
     constexpr size_t ESZ = BF16 ? 2 : 4;
     for (uint32_t tile = wave0; tile < a.ntiles; tile += nwaves) {
         const Tile t = a.tiles[tile];
