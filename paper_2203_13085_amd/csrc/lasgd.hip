@@ -138,8 +138,11 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
 // replica adjacent in launch order, and the
 // streaming hint on every access except z once the state no longer fits the
 // 256 MB memory-side cache.  Items are ordered in chunks of 16384 tiles (16 MB
-// per array): long contiguous runs per replica, and the chunk's z is still
-// near when the next replica needs it.  The split mean wins from K = 8 upwards.
+// per array): long contiguous runs per replica, and the chunk's z is still in
+// L2 when the next replica needs it.  The split mean (256-thread workgroups with
+// LDS) wins from K = 8 upwards; next to one-wave workgroups of a local step it is
+// dispatched sparingly, which keeps the step fast, and split 2 still ends well
+// before the next global update at m = 4 (split 4 trickles until just before it).
 lasgd_tuning default_tuning(const lasgd_ctx &c)
 {
     lasgd_tuning t{};
@@ -147,7 +150,7 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
     t.kper_step = 1;
     t.kper_merge = 1;
     t.max_blocks = -1;
-    t.avg_split = c.K >= 8 ? 4 : 1;
+    t.avg_split = c.K >= 8 ? 2 : 1;
     t.avg_max_blocks = -1;
     t.nontemporal = ((uint64_t)c.K * c.npad * sizeof(float) >= (128ull << 20)) ? 3 : 0;
     t.waves_per_block = 1;
