@@ -217,3 +217,32 @@ def test_overlap_is_race_free_under_load():
         assert_close(dev.ctx.read_state(B.STATE_Z), o.z, "z")
     finally:
         dev.close()
+
+
+def test_rebinding_gradient_buffers():
+    """A caller may re-point a replica at other buffers (e.g. rotating gradient
+    buffers); later steps must read the new ones."""
+    import torch
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=2, numels=(1000, 36))
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    try:
+        o.set_model(x0); dev.load_model(x0)
+        g0, g1 = grads(0), grads(1)
+        dev.load_grads(g0)
+        o.local_step(g0, w.lr); dev.ctx.local_step(w.lr)
+        alt = [torch.zeros_like(t) for t in dev.g]
+        for k in range(w.K):
+            alt[k][dev._idx] = torch.from_numpy(g1[k]).to(dev.dev)
+            dev.ctx.bind(k, [dev.x[k].data_ptr() + int(off) * 4 for off in dev.off[:-1]],
+                         [alt[k].data_ptr() + int(off) * 4 for off in dev.off[:-1]])
+        torch.cuda.synchronize()
+        o.local_step(g1, w.lr); dev.ctx.local_step(w.lr)
+        for k in range(w.K):
+            assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] after rebinding")
+    finally:
+        dev.close()

@@ -112,3 +112,43 @@ def test_inputs_are_pure_functions_of_their_key():
     assert np.all(W.initial_tensor(w, 1) == 1.0) and np.all(W.initial_tensor(w, 2) == 0.0)
     bits = W.to_bf16_bits(a)
     assert np.all(np.abs(W.bf16_bits_to_f32(bits) - a) <= np.abs(a) * 2.0 ** -8)
+
+
+def test_product_path_never_touches_the_oracle():
+    """The HIP path and the oracle share no code: nothing in the package imports,
+    loads or names the oracle, and bench.py reaches it only inside cpu_baseline()."""
+    import ast
+    pkg = os.path.join(ROOT, "paper_2203_13085_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"(import\s+oracle|from\s+oracle|liblasgd_oracle|lasgd_oracle|lasgd_ref64)", text), \
+                    f"{f} reaches for the oracle"
+    tree = ast.parse(open(os.path.join(ROOT, "bench.py")).read())
+    for node in ast.walk(tree):
+        if isinstance(node, ast.FunctionDef):
+            uses = any(isinstance(n, (ast.Import, ast.ImportFrom)) and "oracle" in ast.dump(n) for n in ast.walk(node))
+            if uses:
+                assert node.name == "cpu_baseline", f"bench.py imports the oracle in {node.name}()"
+    top = [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom))]
+    assert not any("oracle" in ast.dump(n) for n in top)
+    # and the oracle does not import the package or load its library
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert not re.search(r"(import\s+paper_2203_13085_amd|from\s+paper_2203_13085_amd|liblasgd_hip|hip_runtime|#include\s+\"lasgd)", text), f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "paper_2203_13085_amd", "no_such_library.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load()
