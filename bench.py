@@ -328,6 +328,25 @@ def main() -> int:
             cycle(ser)
         ser.ctx.sync(); torch.cuda.synchronize()
         ms_serial = 1e3 * (time.perf_counter() - t0) / ns
+        # ---- the same cycle recorded once as a HIP graph and replayed (no per-launch host work) ----
+        ser.close()
+        del ser
+        torch.cuda.empty_cache()
+        gr = ser = make(side=True)
+        gr.prologue(w.lr)
+        gr.ctx.step_merge(w.lr, True)            # close the open cycle: models sent, no mean pending
+        graph = gr.capture_cycle(w.lr, w.m)
+        with torch.cuda.stream(gr.main):
+            for _ in range(args.warmup):
+                graph.replay()
+        gr.ctx.sync(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(gr.main):
+            for _ in range(ns):
+                graph.replay()
+        gr.ctx.sync(); torch.cuda.synchronize()
+        ms_graph = 1e3 * (time.perf_counter() - t0) / ns
+        del graph
         ser.close()
         # time the main stream lost waiting for the mean: how long after the main stream
         # was ready for a step_merge (event before it) the previous mean ended (event after
@@ -340,6 +359,7 @@ def main() -> int:
             "alone_GBps": {"local_step": alg["local_step"] / t_step / 1e6, "step_merge": alg["step_merge"] / t_sm / 1e6,
                            "average": alg["average"] / t_av / 1e6},
             "ms_per_cycle_one_stream": ms_serial,
+            "ms_per_cycle_hip_graph": ms_graph,
             "overlap": {"T_avg_alone_ms": t_av, "T_avg_overlapped_ms": kern_ms["average"], "T_wait_ms": wait,
                         "mean_ended_before_merge_by_ms": -slack, "hidden_frac": 1.0 - min(1.0, wait / t_av),
                         "contention_cost": (ms_per_step - (ms_serial - t_av)) / t_av},

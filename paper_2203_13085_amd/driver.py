@@ -133,5 +133,25 @@ class DeviceReplicas:
         self.ctx.local_step(lr)
         return tau, False
 
+    def capture_cycle(self, lr: float, m: int):
+        """Record one closed cycle as a HIP graph (for workloads whose kernels are so
+        short that launch latency dominates):
+
+            mean (forks to the side stream)  ||  m-1 local steps   ->   fused step + global update (joins)
+
+        The cycle starts from "models sent, no mean pending" (after the prologue's
+        step and snapshot, or after any step_merge) and ends in the same state, so the
+        graph can be replayed back to back; lr is frozen into it.  Replay with
+        `with torch.cuda.stream(self.main): graph.replay()`."""
+        graph = torch.cuda.CUDAGraph()
+        self.ctx.sync()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=self.main):
+            self.ctx.average()
+            for _ in range(m - 1):
+                self.ctx.local_step(lr)
+            self.ctx.step_merge(lr, True)
+        return graph
+
     def close(self) -> None:
         self.ctx.close()

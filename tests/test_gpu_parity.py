@@ -246,3 +246,57 @@ def test_rebinding_gradient_buffers():
             assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] after rebinding")
     finally:
         dev.close()
+
+
+@pytest.mark.parametrize("m", [1, 3])
+def test_graph_replay_equals_eager(m):
+    """A captured cycle replayed several times, with eager library work and host
+    synchronisation between the replays, must give the oracle's state every time."""
+    import torch
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=4, numels=(70000, 5, 1024, 4099), m=m)
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    try:
+        g = grads(1)
+        o.set_model(x0); dev.load_model(x0); dev.load_grads(g)
+        o.local_step(g, w.lr); o.snapshot()
+        dev.ctx.local_step(w.lr); dev.ctx.snapshot()
+        graph = dev.capture_cycle(w.lr, m)        # capturing does not execute
+
+        def oracle_cycle():
+            o.average()
+            for _ in range(m):
+                o.local_step(g, w.lr)
+            o.merge(True)
+
+        for rep in range(5):
+            with torch.cuda.stream(dev.main):
+                graph.replay()
+            oracle_cycle()
+            for k in range(w.K):
+                assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] after replay {rep}")
+                assert_close(dev.ctx.read_state(B.STATE_V, k), o.v[k], f"v[{k}] after replay {rep}")
+                assert_close(dev.ctx.read_state(B.STATE_S, k), o.s[k], f"s[{k}] after replay {rep}")
+            assert_close(dev.ctx.read_state(B.STATE_Z), o.z, f"z after replay {rep}")
+            if rep % 2 == 0:
+                # an eager cycle in between, through the ordinary calls
+                dev.ctx.average()
+                for _ in range(m - 1):
+                    dev.ctx.local_step(w.lr)
+                dev.ctx.step_merge(w.lr, True)
+                oracle_cycle()
+                dev.ctx.sync()
+        # two replays back to back without host synchronisation
+        with torch.cuda.stream(dev.main):
+            graph.replay()
+            graph.replay()
+        oracle_cycle(); oracle_cycle()
+        for k in range(w.K):
+            assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] after back-to-back replays")
+        assert_close(dev.ctx.read_state(B.STATE_Z), o.z, "z after back-to-back replays")
+    finally:
+        dev.close()
