@@ -300,3 +300,132 @@ def test_graph_replay_equals_eager(m):
         assert_close(dev.ctx.read_state(B.STATE_Z), o.z, "z after back-to-back replays")
     finally:
         dev.close()
+
+
+def _same_special(got, ref, what):
+    """Finite values and infinities bit for bit (+0 == -0 aside); NaN where the oracle has NaN
+    (payload and sign of a generated NaN are the processor's business)."""
+    gn, rn = np.isnan(got), np.isnan(ref)
+    np.testing.assert_array_equal(gn, rn, err_msg=f"{what}: NaN positions")
+    ok = ~rn
+    same = (got.view(np.uint32)[ok] == ref.view(np.uint32)[ok]) | ((got[ok] == 0) & (ref[ok] == 0))
+    assert same.all(), f"{what}: {int((~same).sum())} finite values differ"
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_denormals_zeros_infinities_and_nans_are_not_special_cased(storage):
+    """No flushing, no clamping, no checks: denormal parameters and gradients keep their
+    bits, NaN and Inf propagate exactly where the oracle's do."""
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=3, numels=(1024, 37), storage=storage, m=2, T=4)
+    n = w.N
+    rng = np.random.default_rng(11)
+    x0 = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    x0[0:64] = (rng.standard_normal(64) * 1e-41).astype(np.float32)      # denormals
+    x0[100:164] = (rng.standard_normal(64) * 1e-41).astype(np.float32)   # ... that meet denormal gradients
+    x0[64:70] = [0.0, -0.0, 1e30, -1e30, 3e38, 1e-38]
+    x0[70] = np.inf
+    x0[71] = np.nan
+    x0[1030] = -np.inf
+
+    def grads(step):
+        out = []
+        for k in range(w.K):
+            g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+            g[100:164] = (rng.standard_normal(64) * 1e-42).astype(np.float32)
+            g[164] = np.nan if (step == 2 and k == 1) else 0.0
+            g[165] = 3e38                                                  # overflows with momentum
+            out.append(g)
+        return [W.to_bf16_bits(g) for g in out] if storage == "bf16" else out
+
+    if storage == "bf16":
+        x0 = W.to_bf16_bits(x0)
+    wd = [1e-4, 0.0]
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd, storage=storage)
+    try:
+        o.set_model(x0); dev.load_model(x0)
+        g = grads(0)
+        dev.load_grads(g); o.prologue(g, w.lr); dev.prologue(w.lr)
+        tau = 0
+        for i in range(1, w.T + 1):
+            g = grads(i)
+            dev.load_grads(g)
+            o.iteration(g, w.lr, w.m)
+            tau = dev.iteration(w.lr, tau, w.m)
+            for k in range(w.K):
+                _same_special(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x step {i} replica {k}")
+                _same_special(dev.ctx.read_state(B.STATE_V, k), o.v[k], f"v step {i} replica {k}")
+                _same_special(dev.ctx.read_state(B.STATE_S, k), o.s[k], f"s step {i} replica {k}")
+                if storage == "bf16":
+                    got, ref = dev.params(k), o.x16[k]
+                    nan = (ref & 0x7fff) > 0x7f80
+                    np.testing.assert_array_equal(got[~nan], ref[~nan])
+                    assert np.all((got[nan] & 0x7fff) > 0x7f80)
+            _same_special(dev.ctx.read_state(B.STATE_Z), o.z, f"z step {i}")
+        # the run did exercise what it claims to
+        assert np.isnan(o.z).sum() >= 3 and np.isnan(o.x[1]).sum() >= 4
+        if storage == "f32":
+            for arr in (o.x[0][100:164], o.v[0][100:164], o.z[100:164]):
+                assert np.all(np.abs(arr) < 1.2e-38) and np.any(arr != 0)
+    finally:
+        dev.close()
+
+
+def test_two_hundred_steps_stay_bit_identical():
+    """Rounding differences would random-walk over a long run; with the operation order pinned
+    on both sides there are none to accumulate."""
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=4, numels=(6000, 130), m=3, T=200)
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    try:
+        o.set_model(x0); dev.load_model(x0)
+        g = grads(0)
+        dev.load_grads(g); o.prologue(g, w.lr); dev.prologue(w.lr)
+        tau = 0
+        for i in range(1, w.T + 1):
+            g = grads(i)
+            dev.load_grads(g)
+            o.iteration(g, w.lr, w.m)
+            tau = dev.iteration(w.lr, tau, w.m)
+            if i % 50 == 0:
+                for k in range(w.K):
+                    assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x step {i} replica {k}")
+                    assert_close(dev.ctx.read_state(B.STATE_V, k), o.v[k], f"v step {i} replica {k}")
+                assert_close(dev.ctx.read_state(B.STATE_Z), o.z, f"z step {i}")
+    finally:
+        dev.close()
+
+
+def test_k64_masks_reach_the_top_bit():
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=64, numels=(300, 5))
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    c = dev.ctx
+    try:
+        o.set_model(x0); dev.load_model(x0)
+        g = grads(0)
+        dev.load_grads(g)
+        full = (1 << 64) - 1
+        top = (1 << 63) | (1 << 62) | 1
+        o.local_step(g, w.lr); c.local_step_ex(w.lr, full)
+        o.snapshot(); c.snapshot_ex(full)
+        o.average(mask=top); c.average_ex(top)
+        o.local_step(g, 0.01, mask=top); c.local_step_ex(0.01, top)
+        o.merge(True, mask=top); c.merge_ex(top, True)
+        o.average(); c.average()
+        for k in (0, 1, 62, 63):
+            assert_close(c.read_state(B.STATE_X, k), o.x[k], f"x[{k}]")
+            assert_close(c.read_state(B.STATE_S, k), o.s[k], f"s[{k}]")
+        assert_close(c.read_state(B.STATE_Z), o.z, "z")
+    finally:
+        dev.close()
