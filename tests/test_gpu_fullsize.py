@@ -118,3 +118,62 @@ def test_full_size_sampled_columns(cfg):
         dev.close()
         del dev
         torch.cuda.empty_cache()
+
+
+def test_one_huge_tensor_64bit_offsets():
+    """A single tensor of 2^30 + 3 elements (4 GiB per array), K = 2: element offsets inside a
+    tensor, arena offsets and replica strides all exceed 32 bits' worth of bytes; the tail is
+    ragged.  Inputs are drawn on the device; the oracle follows a sample of columns."""
+    import dataclasses
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    n = (1 << 30) + 3
+    w = dataclasses.replace(W.small(K=2, numels=(n,), m=2, T=3), name="huge")
+    rng = np.random.default_rng(9)
+    cols = np.unique(np.concatenate([np.arange(0, 16), np.arange(n - 16, n), rng.integers(0, n, 50000),
+                                     (1 << 29) + np.arange(-8, 8), (1 << 30) + np.arange(-8, 3)]))
+    wd = [w.weight_decay]
+    dev = DeviceReplicas(w, weight_decay=wd)
+    try:
+        say(f"[huge] N={n} K={w.K} sample={cols.size}")
+        dcols = torch.from_numpy(cols).to(dev.dev)
+        gen = torch.Generator(device=dev.dev)
+        gen.manual_seed(77)
+        x0 = torch.randn(n, generator=gen, device=dev.dev) * 0.01
+        for k in range(w.K):
+            dev.x[k][:n].copy_(x0)
+        torch.cuda.synchronize()
+        orc = O32.Oracle(w.K, [cols.size], w.momentum, w.nesterov, wd)
+        orc.set_model(x0[dcols].cpu().numpy())
+        del x0
+
+        def new_grads(step):
+            dev.ctx.sync()
+            out = []
+            for k in range(w.K):
+                gen.manual_seed(1000 * step + k)
+                dev.g[k][:n].normal_(0.0, 1e-3, generator=gen)
+                out.append(dev.g[k][dcols].cpu().numpy())
+            torch.cuda.synchronize()
+            return out
+
+        def check(step):
+            for k in range(w.K):
+                dev.ctx.sync()
+                assert_close(dev.x[k][dcols].cpu().numpy(), orc.x[k], f"x step {step} replica {k}")
+                assert_close(dev.ctx.read_state(B.STATE_V, k)[cols], orc.v[k], f"v step {step} replica {k}")
+                assert_close(dev.ctx.read_state(B.STATE_S, k)[cols], orc.s[k], f"s step {step} replica {k}")
+            assert_close(dev.ctx.read_state(B.STATE_Z)[cols], orc.z, f"z step {step}")
+
+        g = new_grads(0)
+        orc.prologue(g, w.lr); dev.prologue(w.lr)
+        check(0)
+        tau = 0
+        for i in range(1, w.T + 1):
+            g = new_grads(i)
+            orc.iteration(g, w.lr, w.m)
+            tau = dev.iteration(w.lr, tau, w.m)
+        check(w.T)
+    finally:
+        dev.close()
+        del dev
+        torch.cuda.empty_cache()
