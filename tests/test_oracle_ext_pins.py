@@ -480,3 +480,44 @@ def test_dynamic_clock_mistake_is_caught():
     finally:
         O64.run_dynamic = good
     check_e5_dynamic_bruteforce(make64)
+
+
+def test_bf16_storage_variants_of_the_extensions():
+    """bf16 storage changes what is stored, never the arithmetic: the elastic and
+    SGD-AR paths on bf16 inputs equal the fp32 paths fed the widened inputs, and
+    the stored bf16 parameters are torch's rounding of the master."""
+    from paper_2203_13085_amd import workloads as W
+    K, N = 3, 200
+    x0 = W.to_bf16_bits(draws(200, 1, N, 0.1)[0])
+    g = [[W.to_bf16_bits(a) for a in draws(201 + i, K, N, 1e-2)] for i in range(6)]
+    wide = lambda b: W.bf16_bits_to_f32(b)
+
+    def rne(a):
+        return torch.from_numpy(a.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+    # elastic
+    a = O32.Oracle(K, [N], 0.9, True, [1e-3], storage="bf16")
+    b = O32.Oracle(K, [N], 0.9, True, [1e-3])
+    a.set_model(x0); b.set_model(wide(x0))
+    for o, gg in ((a, g), (b, [[wide(t) for t in row] for row in g])):
+        o.local_step(gg[0], 0.1); o.snapshot(); o.average(beta=0.5)
+        for i in range(1, 5):
+            o.local_step(gg[i], 0.1)
+            if i % 2 == 0:
+                o.merge(True, alpha=0.25); o.average(beta=0.5)
+    for k in range(K):
+        np.testing.assert_array_equal(a.x[k], b.x[k])
+        np.testing.assert_array_equal(a.s[k], b.s[k])
+        np.testing.assert_array_equal(a.x16[k], rne(a.x[k]))
+    np.testing.assert_array_equal(a.z, b.z)
+    # SGD-AR
+    a = O32.Oracle(K, [N], 0.9, True, [1e-3], storage="bf16")
+    b = O32.Oracle(K, [N], 0.9, True, [1e-3])
+    a.set_model(x0); b.set_model(wide(x0))
+    for i in range(4):
+        a.sgd_ar_step(g[i], 0.1)
+        b.sgd_ar_step([wide(t) for t in g[i]], 0.1)
+    for k in range(K):
+        np.testing.assert_array_equal(a.x[k], b.x[k])
+        np.testing.assert_array_equal(a.v[k], b.v[k])
+        np.testing.assert_array_equal(a.x16[k], rne(a.x[k]))
