@@ -77,8 +77,11 @@ lasgd_status fail(lasgd_ctx *ctx, lasgd_status st, const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(buf, sizeof buf, fmt, ap);
     va_end(ap);
-    if (ctx) ctx->err = buf;
-    else g_create_error = buf;
+    try {
+        if (ctx) ctx->err = buf;
+        else g_create_error = buf;
+    } catch (...) {       // the message is lost, the status is not
+    }
     return st;
 }
 
@@ -335,9 +338,7 @@ void release(lasgd_ctx *c)
 
 } // namespace
 
-extern "C" {
-
-lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out)
+static lasgd_status create_impl(const lasgd_config *cfg, lasgd_ctx **out)
 {
     if (out) *out = nullptr;
     if (!cfg || !out) return fail(nullptr, LASGD_ERR_INVALID, "NULL argument");
@@ -413,6 +414,20 @@ lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out)
 #undef CREATE_HIP
     *out = c;
     return LASGD_OK;
+}
+
+extern "C" {
+
+// Host containers may throw on exhaustion; nothing may leave through the C ABI.
+lasgd_status lasgd_create(const lasgd_config *cfg, lasgd_ctx **out)
+{
+    try {
+        return create_impl(cfg, out);
+    } catch (...) {
+        if (out) *out = nullptr;
+        try { g_create_error = "out of host memory"; } catch (...) {}
+        return LASGD_ERR_ALLOC;
+    }
 }
 
 lasgd_status lasgd_bind(lasgd_ctx *c, int32_t k, void *const *params, void *const *grads)
@@ -706,7 +721,7 @@ lasgd_status lasgd_read_state(lasgd_ctx *c, int32_t which, int32_t k, int32_t te
     return LASGD_OK;
 }
 
-lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
+static lasgd_status set_tuning_impl(lasgd_ctx *c, const lasgd_tuning *t)
 {
     if (!c) return LASGD_ERR_INVALID;
     if (!t) return fail(c, LASGD_ERR_INVALID, "NULL argument");
@@ -748,6 +763,15 @@ lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
     }
     c->tune = n;
     return LASGD_OK;
+}
+
+lasgd_status lasgd_set_tuning(lasgd_ctx *c, const lasgd_tuning *t)
+{
+    try {
+        return set_tuning_impl(c, t);
+    } catch (...) {
+        return LASGD_ERR_ALLOC;
+    }
 }
 
 lasgd_status lasgd_get_tuning(const lasgd_ctx *c, lasgd_tuning *out)
