@@ -92,7 +92,7 @@ typedef struct {
                               many; inside a chunk replica after replica.  1 = the replicas of a tile are
                               adjacent; <0 = whole replica after whole replica                       */
     int32_t chunk_merge;   /* same for merge / step_merge (a chunk's z tiles are reused K times within
-                              a short window)                                                        */
+                              a short window; multiples of 32 keep a tile on one XCD's L2)           */
     int32_t waves_per_block; /* independent waves per workgroup in the multi-tensor kernels: 1, 2 or 4  */
 } lasgd_tuning;
 

@@ -281,7 +281,10 @@ __device__ __forceinline__ void apply_body(const ApplyArgs &a, const ExtArgs *xa
         // replica group by replica group, so that each replica's arrays are swept in
         // contiguous runs of a.chunk tiles while the chunk's z tiles are reused K times
         // within a short window (chunk = 1: the replicas of one tile are adjacent;
-        // chunk = ntiles: one replica after the other).
+        // chunk = ntiles: one replica after the other).  Workgroups go to the eight
+        // XCDs round-robin, each with its own L2: when a chunk is a multiple of eight
+        // workgroups long, tile j of every replica lands on the same XCD, so only the
+        // first replica's request for a z tile misses that L2.
         uint32_t tile, kg;
         if (item < a.full_items) {
             const uint32_t per = a.chunk * a.kgroups;
