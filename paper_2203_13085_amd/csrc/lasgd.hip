@@ -137,13 +137,13 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
 // Defaults from sweeps on MI355X over the five benchmark workloads: the finest
 // tile (one 128-bit vector per lane), one wave per (tile, replica), a grid that
 // covers all items in one-wave workgroups (the waves are independent, and
-// single-wave groups dispatch and retire with the least friction), tiles of a
-// replica adjacent in launch order, and the
+// single-wave groups dispatch and retire with the least friction), and the
 // streaming hint on every access except z once the state no longer fits the
-// 256 MB memory-side cache.  Items are ordered in chunks of 16384 tiles (16 MB
-// per array): long contiguous runs per replica, and the chunk's z is still in
-// L2 when the next replica needs it.  The split mean (256-thread workgroups with
-// LDS) wins from K = 8 upwards; next to one-wave workgroups of a local step it is
+// 256 MB memory-side cache.  A local step sweeps one replica after the other
+// (the longest contiguous runs); merges take the tiles in chunks of 8192 (8 MB
+// of z per chunk, 1 MB per XCD) so that the chunk's z is still in L2 when the
+// next replica needs it.  The split mean (256-thread workgroups with LDS) wins
+// from K = 8 upwards; next to one-wave workgroups of a local step it is
 // dispatched sparingly, which keeps the step fast, and split 2 still ends well
 // before the next global update at m = 4 (split 4 trickles until just before it).
 lasgd_tuning default_tuning(const lasgd_ctx &c)
@@ -157,8 +157,8 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
     t.avg_max_blocks = -1;
     t.nontemporal = ((uint64_t)c.K * c.npad * sizeof(float) >= (128ull << 20)) ? 3 : 0;
     t.waves_per_block = 1;
-    t.chunk_step = 16384;
-    t.chunk_merge = 16384;
+    t.chunk_step = -1;
+    t.chunk_merge = 8192;
     return t;
 }
 
