@@ -18,7 +18,8 @@
  *   - Errors are return codes; nothing throws or aborts.  A call that fails
  *     enqueues no work and leaves the context unchanged.  The text of the
  *     last failure is available from lasgd_last_error.
- *   - Calls on one context must come from one host thread at a time.
+ *   - Calls on one context must come from one host thread at a time, with the
+ *     device the context was created on current.
  *
  * Memory owned by the caller:  parameters x[k][t] and gradients g[k][t]
  *   (one device buffer per replica k and tensor t, numel[t] elements, 16-byte
