@@ -256,3 +256,59 @@ def test_live_polling_replayed_through_the_oracle(tau_max):
         compare_state(dev, orc, w.T)
     finally:
         dev.close()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_legal_call_sequences(seed):
+    """Randomly drawn, legal sequences of the extended calls (masked steps with
+    per-replica step sizes, partial means, staggered partial merges with and
+    without re-sending, late snapshots, elastic coefficients): device and oracle
+    must agree after every call group."""
+    r = np.random.default_rng(500 + seed)
+    K = int(r.integers(1, 9))
+    storage = "bf16" if seed % 3 == 2 else "f32"
+    numels = tuple(int(n) for n in r.choice([1, 3, 64, 255, 256, 257, 1000, 2049], size=int(r.integers(1, 5))))
+    w = W.small(K=K, numels=numels, storage=storage, momentum=float(r.choice([0.0, 0.9])),
+                nesterov=bool(r.integers(0, 2)))
+    if w.momentum == 0.0:
+        w = __import__("dataclasses").replace(w, nesterov=False)
+    alpha = float(np.float32(r.choice([1.0, 1.0, 0.5])))
+    beta = float(np.float32(r.choice([1.0, 1.0, 0.25])))
+    orc, dev, grads = _pair(w, wd=[float(np.float32(x)) for x in r.choice([0.0, 1e-3], size=len(numels))])
+    c = dev.ctx
+    full = (1 << K) - 1
+    say(f"[fuzz] seed={seed} K={K} numels={numels} storage={storage} alpha={alpha} beta={beta}")
+    try:
+        c.set_elastic(alpha, beta)
+        pending = sent = 0
+        for step in range(12):
+            g = grads(step)
+            dev.load_grads(g)
+            lrs = [float(np.float32(v)) for v in r.uniform(0.01, 0.2, size=K)]
+            mask = int(r.integers(0, full + 1))
+            part = 0
+            if pending and r.random() < 0.6:
+                part = (int(r.integers(1, pending + 1)) & pending) or pending
+                resnap = bool(r.integers(0, 2))
+            if part and r.random() < 0.5:
+                orc.local_step(g, lrs, mask=mask); orc.merge(resnap, mask=part, alpha=alpha)
+                c.step_merge_ex(lrs, mask, part, resnap)
+            else:
+                orc.local_step(g, lrs, mask=mask); c.local_step_ex(lrs, mask)
+                if part:
+                    orc.merge(resnap, mask=part, alpha=alpha); c.merge_ex(part, resnap)
+            if part:
+                pending &= ~part
+                sent = (sent | part) if resnap else (sent & ~part)
+            if not pending:
+                late = full & ~sent
+                if late and r.random() < 0.7:
+                    orc.snapshot(mask=late); c.snapshot_ex(late)
+                    sent |= late
+                if sent and r.random() < 0.8:
+                    p2 = (int(r.integers(1, full + 1)) & sent) or sent
+                    orc.average(mask=p2, beta=beta); c.average_ex(p2)
+                    pending = p2
+            compare_state(dev, orc, step, z_exact=False)
+    finally:
+        dev.close()

@@ -521,3 +521,53 @@ def test_bf16_storage_variants_of_the_extensions():
         np.testing.assert_array_equal(a.x[k], b.x[k])
         np.testing.assert_array_equal(a.v[k], b.v[k])
         np.testing.assert_array_equal(a.x16[k], rne(a.x[k]))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_schedules_two_codes_agree(seed):
+    """Randomly drawn replica counts, parameter lists, optimizer settings, elastic
+    coefficients, participant sets and per-replica step counts: the fp32 C oracle
+    must track the separately written fp64 reference through the whole run."""
+    r = np.random.default_rng(1000 + seed)
+    K = int(r.integers(1, 9))
+    numels = [int(n) for n in r.integers(1, 40, size=int(r.integers(1, 5)))]
+    N = sum(numels)
+    mu = float(np.float32(r.choice([0.0, 0.5, 0.9])))
+    nes = bool(r.integers(0, 2)) and mu > 0
+    wd = [float(np.float32(w)) for w in r.choice([0.0, 1e-4, 1e-2], size=len(numels))]
+    alpha = float(np.float32(r.choice([1.0, 1.0, 0.5, 0.125])))
+    beta = float(np.float32(r.choice([1.0, 1.0, 0.75, 0.25])))
+    a = O32.Oracle(K, numels, mu, nes, wd)
+    b = O64.Ref64(K, numels, mu, nes, wd)
+    x0 = draws(seed, 1, N, 0.3)[0]
+    a.set_model(x0); b.set_model(x0)
+    full = (1 << K) - 1
+    pending = 0
+    sent = 0
+    for step in range(14):
+        g = list(draws(100 * seed + step, K, N, 0.05))
+        lrs = [float(np.float32(v)) for v in r.uniform(0.01, 0.2, size=K)]
+        mask = int(r.integers(0, full + 1))
+        for o in (a, b):
+            o.local_step(g, lrs, mask=mask)
+        if pending and r.random() < 0.6:
+            part = int(r.integers(1, pending + 1)) & pending or pending
+            resnap = bool(r.integers(0, 2))
+            for o in (a, b):
+                o.merge(resnap, mask=part, alpha=alpha)
+            pending &= ~part
+            sent = (sent | part) if resnap else (sent & ~part)
+        if not pending:
+            late = full & ~sent
+            if late and r.random() < 0.7:
+                for o in (a, b):
+                    o.snapshot(mask=late)
+                sent |= late
+            if sent and r.random() < 0.8:
+                part = int(r.integers(1, full + 1)) & sent or sent
+                for o in (a, b):
+                    o.average(mask=part, beta=beta)
+                pending = part
+        for got, ref, nm in ((X(a), X(b), "x"), (V(a), V(b), "v"), (S(a), S(b), "s"), (Z(a)[None], Z(b)[None], "z")):
+            bad = np.abs(got - ref) > 3e-7 + 3e-6 * np.abs(ref)
+            assert not bad.any(), (seed, step, nm, float(np.abs(got - ref).max()))
