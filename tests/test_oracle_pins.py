@@ -384,10 +384,6 @@ def test_pin(make, check):
 
 
 # -------------------------------------------------- planted mistakes (CPU)
-class _M(O64.Ref64):
-    pass
-
-
 def _mutant(name):
     """A wrong variant of the reference; each plants one plausible slip."""
     class M(O64.Ref64):
