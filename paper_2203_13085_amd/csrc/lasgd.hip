@@ -88,9 +88,11 @@ lasgd_status fail(lasgd_ctx *ctx, lasgd_status st, const char *fmt, ...)
 #define LASGD_HIP(ctx, call)                                                                   \
     do {                                                                                       \
         hipError_t e_ = (call);                                                                \
-        if (e_ != hipSuccess)                                                                  \
+        if (e_ != hipSuccess) {                                                                \
+            (void)hipGetLastError(); /* reported here; do not leave it for the next HIP user */ \
             return fail(ctx, e_ == hipErrorOutOfMemory ? LASGD_ERR_ALLOC : LASGD_ERR_HIP,      \
                         "%s failed: %s", #call, hipGetErrorString(e_));                        \
+        }                                                                                      \
     } while (0)
 
 uint64_t round_up(uint64_t a, uint64_t b) { return (a + b - 1) / b * b; }
@@ -126,6 +128,7 @@ lasgd_status upload_tiles(lasgd_ctx *c, int vec)
     hipError_t e = hipMemcpy(d, t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(d);
+        (void)hipGetLastError();
         return fail(c, LASGD_ERR_HIP, "tile table upload failed: %s", hipGetErrorString(e));
     }
     if (c->tiles) (void)hipFree(c->tiles);
@@ -381,6 +384,7 @@ static lasgd_status create_impl(const lasgd_config *cfg, lasgd_ctx **out)
     do {                                                                                       \
         hipError_t e_ = (call);                                                                \
         if (e_ != hipSuccess) {                                                                \
+            (void)hipGetLastError();                                                           \
             lasgd_status st_ = fail(nullptr, e_ == hipErrorOutOfMemory ? LASGD_ERR_ALLOC : LASGD_ERR_HIP, \
                                     "%s failed: %s", #call, hipGetErrorString(e_));            \
             release(c);                                                                        \

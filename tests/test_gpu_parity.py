@@ -429,3 +429,12 @@ def test_k64_masks_reach_the_top_bit():
         assert_close(c.read_state(B.STATE_Z), o.z, "z")
     finally:
         dev.close()
+
+
+def test_allocation_failure_is_reported_not_fatal():
+    """State that cannot fit the GPU (64 replicas of 2^31 - 2^21 parameters: 1.1 TB) is
+    refused with ERR_ALLOC; the library keeps working afterwards."""
+    with pytest.raises(B.LasgdError) as e:
+        B.Context(64, [(1 << 31) - (1 << 21)], momentum=0.9)
+    assert e.value.status == B.ERR_ALLOC, str(e.value)
+    run_parity(W.small(K=2, numels=(300,), m=1, T=2))
