@@ -55,6 +55,56 @@ __global__ __launch_bounds__(256) void stream_kernel(f4 *base, size_t nvec, f4 *
     }
 }
 
+// ---- how the K replicas are spread over waves (the local-step mix, K = 8) ------------------
+// Same bytes, same addresses; only the assignment of work to waves differs.
+struct Rep { f4 *g, *x, *v; size_t stride, nvec; };          // replica k of an array at base + k*stride
+__device__ __forceinline__ void update(f4 g, f4 &x, f4 &v)
+{
+    const f4 g1 = g + 1e-4f * x;
+    v = 0.9f * v + g1;
+    x = x - 0.1f * (g1 + 0.9f * v);
+}
+// one wave per (tile, replica): ORDER 0 = replica after replica, 1 = the replicas of a tile adjacent
+template <int ORDER> __global__ __launch_bounds__(64) void rep_wave_kernel(Rep a)
+{
+    const size_t ntile = a.nvec / 64, item = blockIdx.x;
+    const size_t k = ORDER == 0 ? item / ntile : item % 8, t = ORDER == 0 ? item % ntile : item / 8;
+    const size_t o = k * a.stride + t * 64 + threadIdx.x;
+    f4 g = ld<true>(a.g + o), x = ld<true>(a.x + o), v = ld<true>(a.v + o);
+    update(g, x, v);
+    st<true>(a.v + o, v);
+    st<true>(a.x + o, x);
+}
+// one wave per tile walks the 8 replicas one after the other
+__global__ __launch_bounds__(64) void rep_loop_kernel(Rep a)
+{
+    for (int k = 0; k < 8; ++k) {
+        const size_t o = (size_t)k * a.stride + (size_t)blockIdx.x * 64 + threadIdx.x;
+        f4 g = ld<true>(a.g + o), x = ld<true>(a.x + o), v = ld<true>(a.v + o);
+        update(g, x, v);
+        st<true>(a.v + o, v);
+        st<true>(a.x + o, x);
+    }
+}
+// one wave per tile issues all 24 loads, then all 16 stores
+__global__ __launch_bounds__(64) void rep_all_kernel(Rep a)
+{
+    const size_t o = (size_t)blockIdx.x * 64 + threadIdx.x;
+    f4 g[8], x[8], v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        g[k] = ld<true>(a.g + o + k * a.stride);
+        x[k] = ld<true>(a.x + o + k * a.stride);
+        v[k] = ld<true>(a.v + o + k * a.stride);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        update(g[k], x[k], v[k]);
+        st<true>(a.v + o + k * a.stride, v[k]);
+        st<true>(a.x + o + k * a.stride, x[k]);
+    }
+}
+
 struct Case {
     const char *name;
     int reads, writes, arrays;
@@ -113,6 +163,36 @@ int main()
                 const double moved = (double)(c.reads + c.writes) * bytes;
                 printf("%-30s %5d %5s %10.4f %10.4f %10.0f\n", c.name, bs, nt ? "nt" : "-", ms[0], ms[7], moved / ms[7] / 1e6);
             }
+    // ---- K = 8 replicas of 100 MiB arrays g, x, v (24 x 100 MiB inside the same buffer) ----
+    {
+        const size_t rn = (size_t)25 * 1024 * 1024 / 4;                // vectors per replica-array
+        Rep r{buf, buf + 8 * rn, buf + 16 * rn, rn, rn};
+        const double moved = 5.0 * 8 * rn * sizeof(f4);
+        const unsigned ntile = (unsigned)(rn / 64);
+        printf("\nlocal-step mix over K = 8 replicas of 100 MiB arrays, 64-thread workgroups, hint nt: who does what\n");
+        for (int variant = 0; variant < 4; ++variant) {
+            float ms[11];
+            for (int rep = -2; rep < 11; ++rep) {
+                CK(hipEventRecord(a));
+                if (variant == 0) hipLaunchKernelGGL(rep_wave_kernel<0>, dim3(ntile * 8), dim3(64), 0, 0, r);
+                else if (variant == 1) hipLaunchKernelGGL(rep_wave_kernel<1>, dim3(ntile * 8), dim3(64), 0, 0, r);
+                else if (variant == 2) hipLaunchKernelGGL(rep_loop_kernel, dim3(ntile), dim3(64), 0, 0, r);
+                else hipLaunchKernelGGL(rep_all_kernel, dim3(ntile), dim3(64), 0, 0, r);
+                CK(hipGetLastError());
+                CK(hipEventRecord(b));
+                CK(hipEventSynchronize(b));
+                float t;
+                CK(hipEventElapsedTime(&t, a, b));
+                if (rep >= 0) ms[rep] = t;
+            }
+            for (int i = 0; i < 11; ++i)
+                for (int j = i + 1; j < 11; ++j)
+                    if (ms[j] < ms[i]) { float t = ms[i]; ms[i] = ms[j]; ms[j] = t; }
+            const char *names[] = {"one wave per (tile, replica), replica after replica", "one wave per (tile, replica), replicas of a tile adjacent",
+                                   "one wave per tile, loop over the replicas", "one wave per tile, all 24 loads then all 16 stores"};
+            printf("%-60s %10.4f ms %8.0f GB/s\n", names[variant], ms[5], moved / ms[5] / 1e6);
+        }
+    }
     CK(hipFree(buf));
     CK(hipFree(sink));
     return 0;
