@@ -438,3 +438,21 @@ def test_allocation_failure_is_reported_not_fatal():
         B.Context(64, [(1 << 31) - (1 << 21)], momentum=0.9)
     assert e.value.status == B.ERR_ALLOC, str(e.value)
     run_parity(W.small(K=2, numels=(300,), m=1, T=2))
+
+
+def test_create_destroy_returns_all_device_memory():
+    import torch
+
+    def cycle(i):
+        c = B.Context(4, [1 << 20, 1000, 7], momentum=0.9, storage=B.BF16 if i % 2 else B.F32)
+        c.set_tuning(vec=1 + (i % 2))            # also replaces the tile table once
+        c.close()
+
+    cycle(0); cycle(1)                           # first use loads code objects and runtime pools
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for i in range(40):
+        cycle(i)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert abs(free0 - free1) <= 8 << 20, (free0, free1)
