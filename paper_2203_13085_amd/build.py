@@ -25,19 +25,5 @@ def build_hip(verbose: bool = False) -> str:
     return LIB
 
 
-def build_membench(verbose: bool = False) -> str:
-    """The streaming micro-benchmark the roofline figures are compared with."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(HERE, "membench")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", out, os.path.join(HERE, "csrc", "membench.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return out
-
-
 if __name__ == "__main__":
     print(build_hip(verbose=True))
-    print(build_membench(verbose=True))
