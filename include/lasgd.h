@@ -241,6 +241,31 @@ lasgd_status lasgd_sgd_ar_step(lasgd_ctx *ctx, float lr);
 lasgd_status lasgd_read_state(lasgd_ctx *ctx, int32_t which, int32_t k, int32_t tensor,
                               float *host_dst, int64_t n);
 
+/*
+ * For callers that cannot allocate device memory (code under stream capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the All-Reduce and the
+ * global update of lasgd_average + lasgd_merge in one context-free call on flat
+ * fp32 vectors, with no allocation of any kind on the device.
+ *     z = (1/K) sum_k sent[k]   (fp64 accumulation in replica order, one rounding)
+ *     x[k] <- z + (x[k] - sent[k]);  resnapshot != 0: sent[k] <- x[k]
+ * Same roundings as the context calls.  x, sent: host arrays [K] of device
+ * pointers to n fp32 elements each, 16-byte aligned, all distinct; they are the
+ * caller's, are read during the call (the arrays) and updated in place on the
+ * device (the buffers).  stream: hipStream_t (NULL = default stream); both
+ * kernels are enqueued on it, the call does not wait for them.  z is kept in a
+ * device array built into the library, LASGD_STATIC_MAX_N elements (128 MiB)
+ * per GPU for the life of the process; it is fully rewritten for [0, n) by every
+ * call, so nothing needs clearing, and its contents are not an output.  All calls
+ * on one GPU share that array: two calls whose kernels may overlap on the device
+ * (different streams, no ordering) race.  Error text: lasgd_last_error(NULL).
+ * Errors: INVALID (NULL, K outside 1..64, n < 1, NULL / misaligned / repeated
+ * buffer), UNSUPPORTED (n > LASGD_STATIC_MAX_N), HIP.  A failed call leaves the caller's
+ * buffers untouched.
+ */
+#define LASGD_STATIC_MAX_N (32ll << 20)
+lasgd_status lasgd_global_update_static(int32_t K, int64_t n, float *const *x, float *const *sent,
+                                        int32_t resnapshot, void *stream);
+
 /* Wait until both streams have finished everything this context enqueued. */
 lasgd_status lasgd_sync(lasgd_ctx *ctx);
 
@@ -252,7 +277,8 @@ lasgd_status lasgd_set_tuning(lasgd_ctx *ctx, const lasgd_tuning *t);
 lasgd_status lasgd_get_tuning(const lasgd_ctx *ctx, lasgd_tuning *out);
 
 /* Text of the last failure on this context ("" if none); owned by the context.
- * With ctx == NULL: text of the last lasgd_create failure on this thread. */
+ * With ctx == NULL: text of the last failure of a context-free call (lasgd_create,
+ * lasgd_global_update_static) on this thread. */
 const char *lasgd_last_error(const lasgd_ctx *ctx);
 
 /* Wait for enqueued work, free library-owned memory.  NULL is allowed. */

@@ -27,7 +27,7 @@ EXPORTS = ["lasgd_create", "lasgd_bind", "lasgd_init_master", "lasgd_local_step"
            "lasgd_read_state", "lasgd_sync", "lasgd_set_tuning", "lasgd_get_tuning",
            "lasgd_last_error", "lasgd_destroy", "lasgd_local_step_ex", "lasgd_snapshot_ex",
            "lasgd_average_ex", "lasgd_merge_ex", "lasgd_step_merge_ex", "lasgd_set_elastic",
-           "lasgd_sgd_ar_step"]
+           "lasgd_sgd_ar_step", "lasgd_global_update_static"]
 
 
 class LasgdError(RuntimeError):
@@ -88,6 +88,7 @@ def load() -> ctypes.CDLL:
     L.lasgd_step_merge_ex.argtypes = [P, f32p, u64, u64, i32]
     L.lasgd_set_elastic.argtypes = [P, f32, f32]
     L.lasgd_sgd_ar_step.argtypes = [P, f32]
+    L.lasgd_global_update_static.argtypes = [i32, i64, ctypes.POINTER(P), ctypes.POINTER(P), i32, P]
     L.lasgd_last_error.argtypes = [P]
     L.lasgd_last_error.restype = ctypes.c_char_p
     L.lasgd_destroy.argtypes = [P]
@@ -97,6 +98,22 @@ def load() -> ctypes.CDLL:
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
+
+
+STATIC_MAX_N = 32 << 20
+
+
+def global_update_static(x: Sequence[int], sent: Sequence[int], n: int, resnapshot: bool = True,
+                         stream: Optional[int] = None) -> None:
+    """lasgd_global_update_static: x / sent are device addresses, one per replica."""
+    L = load()
+    K = len(x)
+    assert len(sent) == K
+    xa = (ctypes.c_void_p * max(K, 1))(*x)
+    sa = (ctypes.c_void_p * max(K, 1))(*sent)
+    st = L.lasgd_global_update_static(K, int(n), xa, sa, int(bool(resnapshot)), stream or None)
+    if st != OK:
+        raise LasgdError(st, L.lasgd_last_error(None).decode())
 
 
 class Context:

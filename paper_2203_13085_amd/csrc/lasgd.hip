@@ -16,6 +16,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -799,3 +800,88 @@ void lasgd_destroy(lasgd_ctx *c)
 }
 
 } // extern "C"
+
+// ---- the allocation-free entry point ---------------------------------------
+// z of lasgd_global_update_static lives in this file-scope device array instead
+// of an allocation.  Every GPU that loads the library holds its own copy (128 MiB)
+// until the process ends.  In host code the array's name is only a stand-in for
+// the symbol; its device address is looked up once per device and that pointer
+// is what kernels and copies receive.
+constexpr int64_t kStaticMaxN = LASGD_STATIC_MAX_N;
+static __device__ __align__(256) float scratch[kStaticMaxN];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on first use).
+lasgd_status scratch_for_current_device(float **out)
+{
+    int dev = -1;
+    LASGD_HIP(nullptr, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, LASGD_ERR_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float *p = nullptr;
+        LASGD_HIP(nullptr, hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(nullptr, LASGD_ERR_HIP, "hipGetSymbolAddress returned a NULL address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LASGD_OK;
+}
+
+} // namespace
+
+extern "C" lasgd_status lasgd_global_update_static(int32_t K, int64_t n, float *const *x, float *const *sent,
+                                                   int32_t resnapshot, void *stream)
+{
+    try {
+        if (!x || !sent) return fail(nullptr, LASGD_ERR_INVALID, "NULL pointer array");
+        if (K < 1 || K > kMaxK) return fail(nullptr, LASGD_ERR_INVALID, "K = %d outside 1..%d", K, kMaxK);
+        if (n < 1) return fail(nullptr, LASGD_ERR_INVALID, "n = %lld: nothing to update", (long long)n);
+        if (n > kStaticMaxN)
+            return fail(nullptr, LASGD_ERR_UNSUPPORTED,
+                        "n = %lld exceeds the static buffer of this entry point (LASGD_STATIC_MAX_N = %lld elements); "
+                        "split the vector or use a context",
+                        (long long)n, (long long)kStaticMaxN);
+        FlatArgs a{};
+        for (int32_t k = 0; k < K; ++k) {
+            if (!x[k] || !sent[k]) return fail(nullptr, LASGD_ERR_INVALID, "NULL buffer for replica %d", k);
+            if (((uintptr_t)x[k] | (uintptr_t)sent[k]) & 15u)
+                return fail(nullptr, LASGD_ERR_INVALID, "buffer of replica %d is not 16-byte aligned", k);
+            for (int32_t j = 0; j < k; ++j)
+                if (x[k] == x[j] || sent[k] == sent[j] )
+                    return fail(nullptr, LASGD_ERR_INVALID, "replicas %d and %d share a buffer", j, k);
+            a.x[k] = x[k];
+            a.s[k] = sent[k];
+        }
+        float *z = nullptr;
+        lasgd_status st = scratch_for_current_device(&z);
+        if (st != LASGD_OK) return st;
+        a.z = z;
+        a.n = (uint64_t)n;
+        a.nvec = (uint64_t)n / 4u;
+        a.K = (uint32_t)K;
+        a.use_mul = is_pow2((uint32_t)K) ? 1 : 0;
+        a.inv_k = 1.0 / (double)K;
+        a.k_as_double = (double)K;
+        a.resnap = resnapshot ? 1 : 0;
+        hipStream_t hs = (hipStream_t)stream;
+        // one thread per 128-bit vector, at least enough threads for the scalar tail
+        uint64_t blocks = (a.nvec + 255u) / 256u;
+        if (blocks < 1) blocks = 1;
+        if (blocks > 65535u * 16u) blocks = 65535u * 16u;
+        hipLaunchKernelGGL(flat_mean_kernel, dim3((uint32_t)blocks), dim3(256), 0, hs, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(nullptr, LASGD_ERR_HIP, "mean launch failed: %s", hipGetErrorString(e));
+        hipLaunchKernelGGL(flat_merge_kernel, dim3((uint32_t)blocks, (uint32_t)K), dim3(256), 0, hs, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(nullptr, LASGD_ERR_HIP, "global-update launch failed: %s", hipGetErrorString(e));
+        return LASGD_OK;
+    } catch (...) {
+        return LASGD_ERR_ALLOC;
+    }
+}

@@ -571,4 +571,70 @@ __global__ __launch_bounds__(256) void sgd_ar_kernel(const ApplyArgs a)
     }
 }
 
+// ---- context-free global update on flat fp32 vectors -------------------------
+// For callers that hold no context and may not allocate: the mean (Sec. 3,
+// Eq. 8) of K sent models goes to a buffer the host names, and the global
+// update (Algorithm 1 step 9a-c) reads it back.  Same arithmetic and rounding
+// order as the kernels above; replica pointers travel in the kernel arguments.
+struct FlatArgs {
+    float *x[64];       // local models, n elements each
+    float *s[64];       // sent models
+    float *z;           // the mean, n elements (library scratch)
+    uint64_t n;
+    uint64_t nvec;      // n / 4
+    uint32_t K;
+    int32_t use_mul;    // K is a power of two: multiply by the exact reciprocal
+    double inv_k, k_as_double;
+    int32_t resnap;
+};
+
+__device__ __forceinline__ float flat_mean_of(double acc, const FlatArgs &a)
+{
+    return (float)(a.use_mul ? acc * a.inv_k : acc / a.k_as_double);
+}
+
+__global__ __launch_bounds__(256) void flat_mean_kernel(const FlatArgs a)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (uint64_t i = tid; i < a.nvec; i += stride) {
+        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+        for (uint32_t k = 0; k < a.K; ++k) {
+            const float4 r = ld4<0>(a.s[k] + i * 4u);
+            LASGD_ACC4(r);
+        }
+        st4<0>(a.z + i * 4u, make_float4(flat_mean_of(a0, a), flat_mean_of(a1, a), flat_mean_of(a2, a), flat_mean_of(a3, a)));
+    }
+    // the last n % 4 elements, one thread each
+    const uint64_t e = a.nvec * 4u + tid;
+    if (e < a.n) {
+        double acc = 0.0;
+        for (uint32_t k = 0; k < a.K; ++k) acc += (double)a.s[k][e];
+        a.z[e] = flat_mean_of(acc, a);
+    }
+}
+
+// grid.y = replica; grid.x strides over the 128-bit vectors of that replica
+__global__ __launch_bounds__(256) void flat_merge_kernel(const FlatArgs a)
+{
+    const uint32_t k = blockIdx.y;
+    float *x = a.x[k], *s = a.s[k];
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (uint64_t i = tid; i < a.nvec; i += stride) {
+        float4 xv = ld4<0>(x + i * 4u);
+        const float4 sv = ld4<0>(s + i * 4u);
+        const float4 zv = ld4<0>(a.z + i * 4u);
+        LASGD_FOR4(comp(xv, c) = merge_elem(compv(xv, c), compv(sv, c), compv(zv, c));)
+        st4<0>(x + i * 4u, xv);
+        if (a.resnap) st4<0>(s + i * 4u, xv);
+    }
+    const uint64_t e = a.nvec * 4u + tid;
+    if (e < a.n) {
+        const float xn = merge_elem(x[e], s[e], a.z[e]);
+        x[e] = xn;
+        if (a.resnap) s[e] = xn;
+    }
+}
+
 } // namespace lasgd

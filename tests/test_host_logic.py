@@ -86,6 +86,25 @@ def test_null_arguments():
     L.lasgd_destroy(None)    # allowed
 
 
+def test_static_global_update_validates_before_any_device_call():
+    """No GPU here: every refusal below must come back as a status, not a HIP error."""
+    buf = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    bad = (ctypes.c_void_p * 2)(0x1004, 0x2000)
+    same = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    L = B.load()
+    assert L.lasgd_global_update_static(2, 8, None, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(0, 8, buf, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(65, 8, buf, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(2, 0, buf, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(2, 8, bad, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(2, 8, same, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(2, B.STATIC_MAX_N + 1, buf, same, 1, None) == B.ERR_UNSUPPORTED
+    assert b"LASGD_STATIC_MAX_N" in L.lasgd_last_error(None)
+    text = open(os.path.join(ROOT, "include", "lasgd.h")).read()
+    m = re.search(r"#define LASGD_STATIC_MAX_N \((\d+)ll << (\d+)\)", text)
+    assert int(m.group(1)) << int(m.group(2)) == B.STATIC_MAX_N
+
+
 def test_shape_lists_match_published_architectures():
     # tensor and parameter counts of the torchvision-style models these rules describe
     for shapes, nt, npar in ((W.resnet_shapes(18), 62, 11689512), (W.resnet_shapes(50), 161, 25557032),
