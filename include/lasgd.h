@@ -15,9 +15,13 @@
  *     blocks the host except lasgd_read_state, lasgd_sync and lasgd_destroy.
  *   - All pointers named "device" are HIP device pointers; all others are
  *     host pointers.  Config and pointer arrays are copied during the call.
- *   - Errors are return codes; nothing throws or aborts.  A call that fails
- *     enqueues no work and leaves the context unchanged.  The text of the
- *     last failure is available from lasgd_last_error.
+ *   - Errors are return codes; nothing throws or aborts.  Every argument and
+ *     call-order check precedes the first stream operation, so a call refused
+ *     with INVALID, STATE or UNSUPPORTED enqueues nothing and leaves the context
+ *     unchanged.  A HIP failure in the middle of a call (LASGD_ERR_HIP) can leave
+ *     a stream dependency or a kernel enqueued; the context's call-order state
+ *     then reflects what was enqueued.  The text of the last failure is
+ *     available from lasgd_last_error.
  *   - Calls on one context must come from one host thread at a time, with the
  *     device the context was created on current.
  *
@@ -95,6 +99,12 @@ typedef struct {
     int32_t chunk_merge;   /* same for merge / step_merge (a chunk's z tiles are reused K times within
                               a short window; multiples of 32 keep a tile on one XCD's L2)           */
     int32_t waves_per_block; /* independent waves per workgroup in the multi-tensor kernels: 1, 2 or 4  */
+    int32_t race_probe;    /* debugging aid, 1 = on, <0 = off (default): lasgd_average first fills z with NaN
+                              on the side stream, so a global update that did not wait for the mean shows
+                              as NaN in the parameters.  Results are unchanged when the ordering holds.  */
+    int32_t group_r;       /* replicas one wave takes at a time in the one-workgroup-per-tile kernels
+                              (lasgd_step_merge_average, lasgd_sgd_ar_step): 1, 2 or 4; the workgroup has
+                              ceil(K / group_r) waves, at most 16.  <0 = default (chosen from K)            */
 } lasgd_tuning;
 
 /*
@@ -152,7 +162,9 @@ lasgd_status lasgd_average(lasgd_ctx *ctx);
 /*
  * "All Reduce done?" (Algorithm 1 step 9): *done = 1 if the last average has
  * finished on the device, else 0.  Never blocks.
- * Errors: INVALID (NULL), STATE (no average launched), HIP.
+ * Errors: INVALID (NULL), STATE (no average launched; or the last average was
+ * issued while its stream was being captured into a graph -- a recorded mean
+ * runs whenever the graph is replayed and cannot be polled through this call), HIP.
  */
 lasgd_status lasgd_average_done(lasgd_ctx *ctx, int32_t *done);
 
@@ -171,6 +183,20 @@ lasgd_status lasgd_merge(lasgd_ctx *ctx, int32_t resnapshot);
  * Errors: as lasgd_local_step and lasgd_merge.
  */
 lasgd_status lasgd_step_merge(lasgd_ctx *ctx, float lr, int32_t resnapshot);
+
+/*
+ * One loop iteration with global update AND the next All-Reduce in a single pass
+ * (Algorithm 1 steps 7 and 9a-c, then Sec. 3 Eq. 8 on the models just re-sent):
+ * exactly lasgd_step_merge(lr, 1) followed by lasgd_average, same roundings, but
+ * the K replicas of each tile meet in on-chip memory, so the sent models are not
+ * read back for the mean.  Everything runs on the main stream (after the pending
+ * average), nothing on the side stream; afterwards the new mean counts as
+ * launched, exactly as after lasgd_average.  Meant for cadences with nothing to
+ * overlap the All-Reduce with (a global update every step, tau_max = 1 in Sec. 5.2).
+ * Errors: as lasgd_step_merge, plus STATE when the pending average is partial or
+ * partly merged, or elastic coefficients other than 1 are set.
+ */
+lasgd_status lasgd_step_merge_average(lasgd_ctx *ctx, float lr);
 
 /* ---- extended calls: replicas at their own pace, partial All-Reduce, elastic
  *      coefficients, the SGD All-Reduce comparator ----------------------------

@@ -27,7 +27,7 @@ EXPORTS = ["lasgd_create", "lasgd_bind", "lasgd_init_master", "lasgd_local_step"
            "lasgd_read_state", "lasgd_sync", "lasgd_set_tuning", "lasgd_get_tuning",
            "lasgd_last_error", "lasgd_destroy", "lasgd_local_step_ex", "lasgd_snapshot_ex",
            "lasgd_average_ex", "lasgd_merge_ex", "lasgd_step_merge_ex", "lasgd_set_elastic",
-           "lasgd_sgd_ar_step", "lasgd_global_update_static"]
+           "lasgd_sgd_ar_step", "lasgd_global_update_static", "lasgd_step_merge_average"]
 
 
 class LasgdError(RuntimeError):
@@ -49,7 +49,8 @@ class Tuning(ctypes.Structure):
                 ("max_blocks", ctypes.c_int32), ("avg_split", ctypes.c_int32),
                 ("avg_max_blocks", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
                 ("chunk_step", ctypes.c_int32), ("chunk_merge", ctypes.c_int32),
-                ("waves_per_block", ctypes.c_int32)]
+                ("waves_per_block", ctypes.c_int32), ("race_probe", ctypes.c_int32),
+                ("group_r", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -76,6 +77,7 @@ def load() -> ctypes.CDLL:
     L.lasgd_average_done.argtypes = [P, ctypes.POINTER(i32)]
     L.lasgd_merge.argtypes = [P, i32]
     L.lasgd_step_merge.argtypes = [P, f32, i32]
+    L.lasgd_step_merge_average.argtypes = [P, f32]
     L.lasgd_read_state.argtypes = [P, i32, i32, i32, ctypes.POINTER(f32), i64]
     L.lasgd_sync.argtypes = [P]
     L.lasgd_set_tuning.argtypes = [P, ctypes.POINTER(Tuning)]
@@ -191,6 +193,9 @@ class Context:
 
     def step_merge(self, lr: float, resnapshot: bool = True) -> None:
         self._check(self._L.lasgd_step_merge(self._h, lr, int(resnapshot)))
+
+    def step_merge_average(self, lr: float) -> None:
+        self._check(self._L.lasgd_step_merge_average(self._h, lr))
 
     def _lrs(self, lr):
         vals = [float(lr)] * self.K if np.isscalar(lr) else [float(a) for a in lr]

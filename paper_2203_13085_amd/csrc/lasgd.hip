@@ -62,6 +62,7 @@ struct lasgd_ctx {
     uint64_t snap_mask = 0;      // s[k] holds a model that may be averaged next
     uint64_t pending_mask = 0;   // participants of the launched mean that have not merged yet
     bool avg_ever = false;
+    bool avg_in_graph = false;   // the last mean was recorded into a graph, not executed: evZ says nothing about it
     bool center_valid = false;   // z has been computed at least once
     float alpha = 1.f, beta = 1.f;   // elastic coefficients (Sec. 3, Eq. 5-6); 1, 1 = Algorithm 1
 
@@ -163,6 +164,8 @@ lasgd_tuning default_tuning(const lasgd_ctx &c)
     t.waves_per_block = 1;
     t.chunk_step = -1;
     t.chunk_merge = 8192;
+    t.race_probe = -1;
+    t.group_r = -1;
     return t;
 }
 
@@ -214,13 +217,27 @@ void fill_common(const lasgd_ctx *c, ApplyArgs &a)
     a.n_tensors = (uint32_t)c->n_tensors;
     a.mu = c->mu;
     a.nesterov = c->nesterov;
+    a.use_mul = is_pow2((uint32_t)c->K) ? 1 : 0;
+    a.inv_k = 1.0 / (double)c->K;
+    a.k_as_double = (double)c->K;
 }
 
-// Enqueue one multi-tensor pass on the main stream.  xa == nullptr: every
-// replica takes part, one step size, alpha = 1 (the plain kernels).
-lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const ExtArgs *xa = nullptr)
-{
+// A multi-tensor pass, planned (arguments, grid; everything that can be refused)
+// and then launched on the main stream.  Callers plan before they enqueue any
+// stream dependency, so that a refused call leaves both streams untouched.
+struct ApplyPlan {
     ApplyArgs a{};
+    int op = 0;
+    dim3 grid{1}, bs{64};
+    bool has_ext = false;
+    ExtArgs ext{};
+};
+
+// xa == nullptr: every replica takes part, one step size, alpha = 1 (the plain kernels).
+lasgd_status plan_apply(lasgd_ctx *c, ApplyPlan &p, int op, float lr, int resnap, const ExtArgs *xa = nullptr)
+{
+    if (op < OP_STEP || op > OP_INIT) return fail(c, LASGD_ERR_INVALID, "unknown op %d", op);
+    ApplyArgs &a = p.a;
     fill_common(c, a);
     int kper = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.kper_merge : c->tune.kper_step;
     if (kper < 1) kper = 1;
@@ -242,35 +259,93 @@ lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const Ext
     const uint32_t wpb = (uint32_t)c->tune.waves_per_block;
     uint64_t blocks = (nitems + wpb - 1) / wpb;
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
-    const dim3 grid((uint32_t)blocks), bs(64u * wpb);
+    p.op = op;
+    p.grid = dim3((uint32_t)blocks);
+    p.bs = dim3(64u * wpb);
+    p.has_ext = xa != nullptr;
+    if (xa) p.ext = *xa;
+    return LASGD_OK;
+}
+
+lasgd_status launch_apply(lasgd_ctx *c, const ApplyPlan &p)
+{
     const bool bf16 = c->storage == LASGD_BF16;
     const int vec = c->tune.vec, nt = c->tune.nontemporal;
+    const ExtArgs *xa = p.has_ext ? &p.ext : nullptr;
     hipError_t e = hipSuccess;
-    switch (op) {
-    case OP_STEP: e = launch_op<OP_STEP>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
-    case OP_MERGE: e = launch_op<OP_MERGE>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
-    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
-    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(a, xa, grid, bs, c->main, vec, nt, bf16); break;
-    case OP_INIT: e = launch_vec<OP_INIT, true>(a, nullptr, grid, bs, c->main, vec, nt); break;
-    default: return fail(c, LASGD_ERR_INVALID, "unknown op %d", op);
+    switch (p.op) {
+    case OP_STEP: e = launch_op<OP_STEP>(p.a, xa, p.grid, p.bs, c->main, vec, nt, bf16); break;
+    case OP_MERGE: e = launch_op<OP_MERGE>(p.a, xa, p.grid, p.bs, c->main, vec, nt, bf16); break;
+    case OP_STEP_MERGE: e = launch_op<OP_STEP_MERGE>(p.a, xa, p.grid, p.bs, c->main, vec, nt, bf16); break;
+    case OP_SNAPSHOT: e = launch_op<OP_SNAPSHOT>(p.a, xa, p.grid, p.bs, c->main, vec, nt, bf16); break;
+    default: e = launch_vec<OP_INIT, true>(p.a, nullptr, p.grid, p.bs, c->main, vec, nt); break;
     }
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return LASGD_OK;
 }
 
-template <bool BF16>
-hipError_t launch_sgd_ar(const ApplyArgs &a, dim3 grid, dim3 bs, hipStream_t st, int vec, int nt)
+lasgd_status enqueue_apply(lasgd_ctx *c, int op, float lr, int resnap, const ExtArgs *xa = nullptr)
 {
-#define LASGD_AR(V)                                                                             \
-    do {                                                                                        \
-        if (nt & 3) hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 3>), grid, bs, 0, st, a); \
-        else hipLaunchKernelGGL((sgd_ar_kernel<V, BF16, 0>), grid, bs, 0, st, a);        \
+    ApplyPlan p;
+    lasgd_status st = plan_apply(c, p, op, lr, resnap, xa);
+    if (st != LASGD_OK) return st;
+    return launch_apply(c, p);
+}
+
+// The replica-group kernels: one workgroup per tile, W waves, R replicas per wave.
+struct GroupShape {
+    uint32_t R, W, passes;
+    dim3 grid, bs;
+    size_t lds;
+};
+
+GroupShape group_shape(const lasgd_ctx *c, int kind)
+{
+    GroupShape g{};
+    const uint32_t K = (uint32_t)c->K;
+    // replicas a wave takes at a time (measured on MI355X).  Every wave of the SGD-AR kernel
+    // repeats the fp64 sum, so it prefers fewer, fatter waves sooner than the fused update,
+    // whose sum is shared out; beyond 16 replicas both do best with 8-wave workgroups.
+    if (kind == 0) g.R = K < 4u ? 1u : K <= 16u ? 2u : 4u;
+    else g.R = K <= kGroupWaves ? 1u : 4u;
+    if (c->tune.group_r > 0) g.R = (uint32_t)c->tune.group_r;
+    if (g.R > K) g.R = K >= 4 ? 4 : K >= 2 ? 2 : 1;
+    g.W = (K + g.R - 1) / g.R;
+    if (g.W > kGroupWaves) g.W = kGroupWaves;
+    g.passes = (K + g.W * g.R - 1) / (g.W * g.R);
+    uint64_t blocks = c->ntiles;
+    if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
+    g.grid = dim3((uint32_t)blocks);
+    g.bs = dim3(64u * g.W);
+    g.lds = (size_t)K * 256u * sizeof(float);
+    return g;
+}
+
+template <int KIND, bool BF16, int NT>
+hipError_t launch_group_r(const ApplyArgs &a, const GroupShape &g, hipStream_t st)
+{
+#define LASGD_GROUP(RR)                                                                                  \
+    do {                                                                                                 \
+        if constexpr (KIND == 0) hipLaunchKernelGGL((sgd_ar_kernel<RR, BF16, NT>), g.grid, g.bs, g.lds, st, a, g.passes); \
+        else hipLaunchKernelGGL((step_merge_mean_kernel<RR, BF16, NT>), g.grid, g.bs, g.lds, st, a, g.passes);         \
     } while (0)
-    if (vec == 1) LASGD_AR(1);
-    else if (vec == 2) LASGD_AR(2);
-    else LASGD_AR(4);
-#undef LASGD_AR
+    if (g.R == 1) LASGD_GROUP(1);
+    else if (g.R == 2) LASGD_GROUP(2);
+    else LASGD_GROUP(4);
+#undef LASGD_GROUP
     return hipGetLastError();
+}
+
+// kind 0: SGD All-Reduce step; kind 1: fused step + global update + next mean
+hipError_t launch_group(int kind, const ApplyArgs &a, const GroupShape &g, hipStream_t st, bool bf16, int nt)
+{
+    const bool hint = (nt & 3) != 0;
+    if (kind == 0) {
+        if (bf16) return hint ? launch_group_r<0, true, 3>(a, g, st) : launch_group_r<0, true, 0>(a, g, st);
+        return hint ? launch_group_r<0, false, 3>(a, g, st) : launch_group_r<0, false, 0>(a, g, st);
+    }
+    if (bf16) return hint ? launch_group_r<1, true, 3>(a, g, st) : launch_group_r<1, true, 0>(a, g, st);
+    return hint ? launch_group_r<1, false, 3>(a, g, st) : launch_group_r<1, false, 0>(a, g, st);
 }
 
 template <bool EXT>
@@ -541,24 +616,45 @@ static lasgd_status do_snapshot(lasgd_ctx *c, uint64_t mask)
     return LASGD_OK;
 }
 
+// Is this stream recording into a graph rather than executing?
+static bool is_capturing(hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs != hipStreamCaptureStatusNone;
+}
+
 static lasgd_status do_average(lasgd_ctx *c, uint64_t mask)
 {
+    // every refusal comes before the first event or launch
     lasgd_status st = check_mask(c, mask, false, "mask");
     if (st != LASGD_OK) return st;
     if (c->pending_mask) return fail(c, LASGD_ERR_STATE, "the previous average has not been merged by all its participants");
     if (mask & ~c->snap_mask) return fail(c, LASGD_ERR_STATE, "no snapshot to average for some of these replicas");
+    const bool captured = is_capturing(c->main);
     if (c->side != c->main) {
         LASGD_HIP(c, hipEventRecord(c->evA, c->main));
         LASGD_HIP(c, hipStreamWaitEvent(c->side, c->evA, 0));
     }
     // the first mean initialises the centre: there is no earlier z to blend with
     const bool elastic = c->beta != 1.f && c->center_valid;
+    if (c->tune.race_probe > 0 && !elastic) {
+        // debugging aid: z is poisoned on the side stream just before the mean rewrites it
+        hipLaunchKernelGGL(poison_kernel, dim3(1024), dim3(256), 0, c->side, c->z, c->npad);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "poison launch failed: %s", hipGetErrorString(e));
+    }
     st = enqueue_average(c, mask, elastic);
     if (st != LASGD_OK) return st;
-    LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
+    // from here on the side stream reads s and writes z: the state says so even if the event below fails
     c->pending_mask = mask;
     c->avg_ever = true;
     c->center_valid = true;
+    c->avg_in_graph = captured;
+    LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
     return LASGD_OK;
 }
 
@@ -573,15 +669,19 @@ static lasgd_status do_merge(lasgd_ctx *c, int op, const float *lr_k, float lr, 
     if (!c->pending_mask) return fail(c, LASGD_ERR_STATE, "no average launched since the last merge");
     if (merge_mask & ~c->pending_mask)
         return fail(c, LASGD_ERR_STATE, "some of these replicas did not take part in the pending average or have merged already");
-    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
     ExtArgs x{};
     float same[64];
     for (int k = 0; k < 64; ++k) same[k] = lr;
     const bool uniform = fill_ext(c, x, lr_k ? lr_k : same, step_mask, merge_mask);
     const bool plain = merge_mask == c->all && c->alpha == 1.f &&
                        (op == OP_MERGE || (step_mask == c->all && uniform));
-    if (plain) st = enqueue_apply(c, op, lr_k ? lr_k[0] : lr, resnapshot ? 1 : 0);
-    else st = enqueue_apply(c, op, 0.f, resnapshot ? 1 : 0, &x);
+    ApplyPlan p;
+    if (plain) st = plan_apply(c, p, op, lr_k ? lr_k[0] : lr, resnapshot ? 1 : 0);
+    else st = plan_apply(c, p, op, 0.f, resnapshot ? 1 : 0, &x);
+    if (st != LASGD_OK) return st;
+    // nothing can be refused any more: now the main stream waits for z
+    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    st = launch_apply(c, p);
     if (st != LASGD_OK) return st;
     c->pending_mask &= ~merge_mask;
     if (resnapshot) c->snap_mask |= merge_mask;
@@ -631,6 +731,8 @@ lasgd_status lasgd_average_done(lasgd_ctx *c, int32_t *done)
     if (!c) return LASGD_ERR_INVALID;
     if (!done) return fail(c, LASGD_ERR_INVALID, "NULL argument");
     if (!c->avg_ever) return fail(c, LASGD_ERR_STATE, "no average has been launched");
+    if (c->avg_in_graph)
+        return fail(c, LASGD_ERR_STATE, "the last average was recorded into a graph: its completion cannot be polled here");
     hipError_t e = hipEventQuery(c->evZ);
     if (e == hipSuccess) *done = 1;
     else if (e == hipErrorNotReady) *done = 0;
@@ -682,13 +784,37 @@ lasgd_status lasgd_sgd_ar_step(lasgd_ctx *c, float lr)
     ApplyArgs a{};
     fill_common(c, a);
     a.neg_lr = -lr;
-    const uint32_t wpb = (uint32_t)c->tune.waves_per_block;
-    uint64_t blocks = ((uint64_t)a.ntiles + wpb - 1) / wpb;
-    if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;
-    const dim3 grid((uint32_t)blocks), bs(64u * wpb);
-    hipError_t e = c->storage == LASGD_BF16 ? launch_sgd_ar<true>(a, grid, bs, c->main, c->tune.vec, c->tune.nontemporal)
-                                            : launch_sgd_ar<false>(a, grid, bs, c->main, c->tune.vec, c->tune.nontemporal);
+    const GroupShape g = group_shape(c, 0);
+    hipError_t e = launch_group(0, a, g, c->main, c->storage == LASGD_BF16, c->tune.nontemporal);
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return LASGD_OK;
+}
+
+lasgd_status lasgd_step_merge_average(lasgd_ctx *c, float lr)
+{
+    if (!c) return LASGD_ERR_INVALID;
+    lasgd_status st = check_ready_to_step(c, lr);
+    if (st != LASGD_OK) return st;
+    if (!c->pending_mask) return fail(c, LASGD_ERR_STATE, "no average launched since the last merge");
+    if (c->pending_mask != c->all)
+        return fail(c, LASGD_ERR_STATE, "the pending average is partial or partly merged: use lasgd_step_merge_ex and lasgd_average_ex");
+    if (c->alpha != 1.f || c->beta != 1.f)
+        return fail(c, LASGD_ERR_STATE, "elastic coefficients are set: use lasgd_step_merge and lasgd_average");
+    ApplyArgs a{};
+    fill_common(c, a);
+    a.neg_lr = -lr;
+    a.resnap = 1;
+    const GroupShape g = group_shape(c, 1);
+    const bool captured = is_capturing(c->main);
+    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    hipError_t e = launch_group(1, a, g, c->main, c->storage == LASGD_BF16, c->tune.nontemporal);
+    if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    // every replica has merged and re-sent, and the mean of the sent models is (being) written to z
+    // on the main stream: the same state as after lasgd_step_merge(lr, 1) + lasgd_average
+    c->snap_mask = c->all;
+    c->pending_mask = c->all;
+    c->avg_in_graph = captured;
+    LASGD_HIP(c, hipEventRecord(c->evZ, c->main));
     return LASGD_OK;
 }
 
@@ -760,6 +886,12 @@ static lasgd_status set_tuning_impl(lasgd_ctx *c, const lasgd_tuning *t)
     }
     if (t->chunk_step) n.chunk_step = t->chunk_step < 0 ? -1 : t->chunk_step;
     if (t->chunk_merge) n.chunk_merge = t->chunk_merge < 0 ? -1 : t->chunk_merge;
+    if (t->race_probe) n.race_probe = t->race_probe > 0 ? 1 : -1;
+    if (t->group_r) {
+        if (t->group_r > 0 && t->group_r != 1 && t->group_r != 2 && t->group_r != 4)
+            return fail(c, LASGD_ERR_INVALID, "group_r must be 1, 2 or 4 (or negative for the default)");
+        n.group_r = t->group_r < 0 ? -1 : t->group_r;
+    }
     lasgd_status st = lasgd_sync(c);
     if (st != LASGD_OK) return st;
     if (n.vec != c->tune.vec) {

@@ -46,7 +46,7 @@ struct ApplyArgs {
     float *x32;             // bf16 storage only: fp32 master, [K][npad]
     float *v;               // momentum,     [K][npad]
     float *s;               // sent models,  [K][npad]
-    const float *z;         // mean,         [npad]
+    float *z;               // mean,         [npad] (written only by the fused step+update+mean kernel)
     uint64_t npad;          // elements per replica in the arenas
     uint32_t ntiles, K, n_tensors;
     uint32_t kper;          // replicas a wave handles back to back
@@ -58,6 +58,9 @@ struct ApplyArgs {
     uint32_t full_items;    // (ntiles / chunk) * chunk * kgroups
     uint32_t tail_first;    // first tile of the last, shorter chunk
     uint32_t tail_chunk;    // its length (>= 1 even when unused)
+    // the replica-group kernels finish a mean over all K replicas themselves
+    int32_t use_mul;        // K is a power of two: multiply by the exact reciprocal
+    double inv_k, k_as_double;
 };
 
 // What the extended entry points add: replicas that sit a call out, a step size
@@ -507,68 +510,269 @@ __global__ __launch_bounds__(256) void average_split_kernel(const AvgArgs a)
     }
 }
 
-// ---- SGD All-Reduce comparator (Sec. 2; "SGD-AR" of Table 1) -----------------
-// One wave per tile: the K gradients of the tile are averaged (fp64 in replica
-// order, one rounding to fp32) and every replica takes the local update with
-// that mean gradient.  Same 20 bytes per replica-parameter as a local step.
-template <int VEC, bool BF16, int NT>
-__global__ __launch_bounds__(256) void sgd_ar_kernel(const ApplyArgs a)
+// ---- replica-group kernels ----------------------------------------------------
+// Two operations need all K replicas of an element at once: the mean gradient of
+// the SGD All-Reduce comparator, and the next mean z when it is computed in the
+// same pass as the global update.  Both use one workgroup per tile with one wave
+// per replica (wave w owns replicas w, w + W, ... when K exceeds the W = 16 waves
+// a workgroup can hold).  Every wave streams its own replica's arrays exactly as
+// the one-wave-per-(tile, replica) kernels do, the K values of each element meet
+// in LDS as fp32 (exact), and the sum runs in fp64 in replica order, so the result
+// is bit-identical to the in-order mean.  The tile is processed in rows of 256
+// elements; LDS holds one row per replica (K KiB).
+constexpr uint32_t kGroupWaves = 16;
+
+// Elements [e0, e0+4) of one row for this lane; n = how many of them exist.
+template <int NT, bool FULL> __device__ __forceinline__ float4 row_ld(const float *p, uint32_t e0, uint32_t n)
 {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wpb = blockDim.x >> 6;
-    const uint32_t wave0 = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + (threadIdx.x >> 6));
-    const uint32_t nwaves = gridDim.x * wpb;
+    if (FULL || n == 4u) return ld4<NT>(p + e0);
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n > 0u) r.x = p[e0];
+    if (n > 1u) r.y = p[e0 + 1u];
+    if (n > 2u) r.z = p[e0 + 2u];
+    return r;
+}
+template <int NT, bool FULL> __device__ __forceinline__ float4 row_ld16(const uint16_t *p, uint32_t e0, uint32_t n)
+{
+    if (FULL || n == 4u) return widen4(ld2<NT>(p + e0));
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n > 0u) r.x = bf16_widen(p[e0]);
+    if (n > 1u) r.y = bf16_widen(p[e0 + 1u]);
+    if (n > 2u) r.z = bf16_widen(p[e0 + 2u]);
+    return r;
+}
+template <int NT, bool FULL> __device__ __forceinline__ void row_st(float *p, uint32_t e0, uint32_t n, float4 a)
+{
+    if (FULL || n == 4u) { st4<NT>(p + e0, a); return; }
+    if (n > 0u) p[e0] = a.x;
+    if (n > 1u) p[e0 + 1u] = a.y;
+    if (n > 2u) p[e0 + 2u] = a.z;
+}
+template <int NT, bool FULL> __device__ __forceinline__ void row_st16(uint16_t *p, uint32_t e0, uint32_t n, float4 a)
+{
+    if (FULL || n == 4u) { st2<NT>(p + e0, round4(a)); return; }
+    if (n > 0u) p[e0] = (uint16_t)bf16_round(a.x);
+    if (n > 1u) p[e0 + 1u] = (uint16_t)bf16_round(a.y);
+    if (n > 2u) p[e0 + 2u] = (uint16_t)bf16_round(a.z);
+}
+
+__device__ __forceinline__ float group_mean_of(double acc, const ApplyArgs &a)
+{
+    return (float)(a.use_mul ? acc * a.inv_k : acc / a.k_as_double);
+}
+
+// Where replica k keeps one tile: the fp32 model (the caller's buffer, or the master
+// copy for bf16 storage), the caller's 16-bit parameters and gradient, v and s.
+template <bool BF16> struct ReplicaTile {
+    float *xf, *v, *s;
+    uint16_t *x16;
+    const void *g;
+};
+template <bool BF16>
+__device__ __forceinline__ ReplicaTile<BF16> replica_tile(const ApplyArgs &a, const Tile &t, uint32_t k)
+{
     constexpr size_t ESZ = BF16 ? 2 : 4;
-    for (uint32_t tile = wave0; tile < a.ntiles; tile += nwaves) {
-        const Tile t = load_tile(a.tiles + tile);
-#pragma unroll 1
-        for (int j = 0; j < VEC; ++j) {                   // one 256-element row of the tile at a time
-        const uint32_t e0 = j * 256u + lane * 4u;
-        const uint32_t n = (e0 >= t.count) ? 0u : (t.count - e0 < 4u) ? t.count - e0 : 4u;
-        const bool vec_ok = (n == 4u);
-        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-        for (uint32_t k = 0; k < a.K; ++k) {
-            const char *gu = load_ptr(a.gptr, (size_t)k * a.n_tensors + t.tensor) + t.toff * ESZ;
-            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vec_ok) {
-                r = BF16 ? widen4(ld2<NT>(reinterpret_cast<const uint16_t *>(gu) + e0))
-                         : ld4<NT>(reinterpret_cast<const float *>(gu) + e0);
-            } else {
-                for (uint32_t i = 0; i < n; ++i) {
-                    const float ge = BF16 ? bf16_widen(reinterpret_cast<const uint16_t *>(gu)[e0 + i])
-                                          : reinterpret_cast<const float *>(gu)[e0 + i];
-                    if (i == 0) r.x = ge; else if (i == 1) r.y = ge; else r.z = ge;
-                }
-            }
-            LASGD_ACC4(r);
+    const size_t pi = (size_t)k * a.n_tensors + t.tensor;
+    const size_t ao = (size_t)k * a.npad + t.aoff;
+    char *xu = load_ptr(a.xptr, pi) + t.toff * ESZ;
+    ReplicaTile<BF16> r;
+    r.xf = BF16 ? a.x32 + ao : reinterpret_cast<float *>(xu);
+    r.x16 = reinterpret_cast<uint16_t *>(xu);
+    r.v = a.v + ao;
+    r.s = a.s + ao;
+    r.g = load_ptr(a.gptr, pi) + t.toff * ESZ;
+    return r;
+}
+template <bool BF16, int NT, bool FULL>
+__device__ __forceinline__ float4 row_ld_grad(const void *g, uint32_t e0, uint32_t n)
+{
+    if constexpr (BF16) return row_ld16<NT, FULL>(static_cast<const uint16_t *>(g), e0, n);
+    else return row_ld<NT, FULL>(static_cast<const float *>(g), e0, n);
+}
+
+// A wave owns replicas w + q*W, q = 0, 1, ...; it takes them R at a time ("pass").
+// A wave whose pass runs past K re-reads replica K-1 and keeps nothing of it, so
+// that the loads of a pass stay free of branches.
+
+// SGD All-Reduce comparator (Sec. 2; "SGD-AR" of Table 1), one row of a tile:
+// the K gradients are averaged (fp64 in replica order, one rounding to fp32) and
+// every replica takes the local update with that mean gradient.  Same 20 bytes
+// per replica-parameter as a local step.
+template <int R, bool BF16, int NT, bool FULL>
+__device__ __forceinline__ void sgd_ar_row(const ApplyArgs &a, const Tile &t, float *lds, uint32_t row,
+                                           uint32_t w, uint32_t W, uint32_t passes, uint32_t lane)
+{
+    const uint32_t e0 = row * 256u + lane * 4u;
+    const uint32_t n = FULL ? 4u : (e0 >= t.count) ? 0u : (t.count - e0 < 4u) ? t.count - e0 : 4u;
+    // first pass: the model loads are issued with the gradient loads, ahead of the exchange
+    float4 x[R], v[R];
+    ReplicaTile<BF16> rt[R];
+    bool mine[R];
+    {
+        float4 g[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t kw = w + (uint32_t)r * W;
+            mine[r] = kw < a.K;
+            rt[r] = replica_tile<BF16>(a, t, mine[r] ? kw : a.K - 1u);
+            g[r] = row_ld_grad<BF16, NT, FULL>(rt[r].g, e0, n);
+            x[r] = row_ld<NT, FULL>(rt[r].xf, e0, n);
+            v[r] = row_ld<NT, FULL>(rt[r].v, e0, n);
         }
-        const double kd = (double)a.K;
-        const float4 gbar = make_float4((float)(a0 / kd), (float)(a1 / kd), (float)(a2 / kd), (float)(a3 / kd));
-        for (uint32_t k = 0; k < a.K; ++k) {
-            const size_t pi = (size_t)k * a.n_tensors + t.tensor;
-            char *xu = load_ptr(a.xptr, pi) + t.toff * ESZ;
-            const size_t ao = (size_t)k * a.npad + t.aoff;
-            float *xf = BF16 ? a.x32 + ao : reinterpret_cast<float *>(xu);
-            uint16_t *x16 = reinterpret_cast<uint16_t *>(xu);
-            float *v = a.v + ao;
-            if (vec_ok) {
-                float4 x = ld4<NT>(xf + e0), vv = ld4<NT>(v + e0);
-                LASGD_FOR4(step_elem(comp(x, c), comp(vv, c), compv(gbar, c), t.wd, a.mu, a.neg_lr, a.nesterov);)
-                st4<NT>(v + e0, vv);
-                st4<NT>(xf + e0, x);
-                if constexpr (BF16) st2<NT>(x16 + e0, round4(x));
-            } else {
-                for (uint32_t i = 0; i < n; ++i) {
-                    float xe = xf[e0 + i], ve = v[e0 + i];
-                    step_elem(xe, ve, compv(gbar, (int)i), t.wd, a.mu, a.neg_lr, a.nesterov);
-                    v[e0 + i] = ve;
-                    xf[e0 + i] = xe;
-                    if constexpr (BF16) x16[e0 + i] = (uint16_t)bf16_round(xe);
-                }
-            }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (mine[r]) *reinterpret_cast<float4 *>(lds + (size_t)(w + (uint32_t)r * W) * 256u + lane * 4u) = g[r];
+    }
+    for (uint32_t p = 1; p < passes; ++p) {
+        float4 g[R];
+        uint32_t kw[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            kw[r] = w + (p * R + (uint32_t)r) * W;
+            const ReplicaTile<BF16> q = replica_tile<BF16>(a, t, kw[r] < a.K ? kw[r] : a.K - 1u);
+            g[r] = row_ld_grad<BF16, NT, FULL>(q.g, e0, n);
         }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (kw[r] < a.K) *reinterpret_cast<float4 *>(lds + (size_t)kw[r] * 256u + lane * 4u) = g[r];
+    }
+    __syncthreads();
+    // every wave sums the row itself: handing the sum to a few waves and passing the result
+    // round through LDS costs a second barrier and measured slower than the repeated fp64 adds
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    for (uint32_t k = 0; k < a.K; ++k) {
+        const float4 q = *reinterpret_cast<const float4 *>(lds + (size_t)k * 256u + lane * 4u);
+        LASGD_ACC4(q);
+    }
+    const float4 gbar = make_float4(group_mean_of(a0, a), group_mean_of(a1, a), group_mean_of(a2, a), group_mean_of(a3, a));
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        LASGD_FOR4(step_elem(comp(x[r], c), comp(v[r], c), compv(gbar, c), t.wd, a.mu, a.neg_lr, a.nesterov);)
+        if (mine[r]) {
+            row_st<NT, FULL>(rt[r].v, e0, n, v[r]);
+            row_st<NT, FULL>(rt[r].xf, e0, n, x[r]);
+            if constexpr (BF16) row_st16<NT, FULL>(rt[r].x16, e0, n, x[r]);
         }
     }
+    for (uint32_t p = 1; p < passes; ++p) {
+        ReplicaTile<BF16> q[R];
+        float4 xx[R], vv[R];
+        bool ok[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t kw = w + (p * R + (uint32_t)r) * W;
+            ok[r] = kw < a.K;
+            q[r] = replica_tile<BF16>(a, t, ok[r] ? kw : a.K - 1u);
+            xx[r] = row_ld<NT, FULL>(q[r].xf, e0, n);
+            vv[r] = row_ld<NT, FULL>(q[r].v, e0, n);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            LASGD_FOR4(step_elem(comp(xx[r], c), comp(vv[r], c), compv(gbar, c), t.wd, a.mu, a.neg_lr, a.nesterov);)
+            if (ok[r]) {
+                row_st<NT, FULL>(q[r].v, e0, n, vv[r]);
+                row_st<NT, FULL>(q[r].xf, e0, n, xx[r]);
+                if constexpr (BF16) row_st16<NT, FULL>(q[r].x16, e0, n, xx[r]);
+            }
+        }
+    }
+    __syncthreads();                 // the next row reuses the LDS buffer
+}
+
+template <int R, bool BF16, int NT>
+__global__ __launch_bounds__(1024) void sgd_ar_kernel(const ApplyArgs a, const uint32_t passes)
+{
+    extern __shared__ float lds[];                        // [K][256]
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t W = blockDim.x >> 6;
+    for (uint32_t tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+        const Tile t = load_tile(a.tiles + tile);
+        const uint32_t rows = (t.count + 255u) >> 8;
+        for (uint32_t row = 0; row < rows; ++row) {
+            if (t.count - row * 256u >= 256u) sgd_ar_row<R, BF16, NT, true>(a, t, lds, row, w, W, passes, lane);
+            else sgd_ar_row<R, BF16, NT, false>(a, t, lds, row, w, W, passes, lane);
+        }
+    }
+}
+
+// Steps 7 and 9a-c of Algorithm 1 and the next All-Reduce (Sec. 3, Eq. 8) in one
+// pass: every replica takes its local update, then the global update with the
+// pending z, re-sends (s <- x), and the tile's next z -- the mean of the models
+// just sent -- is written over the old one.  Only this workgroup touches the
+// tile's z, and all its waves have used the old values before the barrier.
+// Same roundings as step_merge followed by the in-order mean.
+template <int R, bool BF16, int NT, bool FULL>
+__device__ __forceinline__ void step_merge_mean_row(const ApplyArgs &a, const Tile &t, float *lds, uint32_t row,
+                                                    uint32_t w, uint32_t W, uint32_t passes, uint32_t lane)
+{
+    const uint32_t e0 = row * 256u + lane * 4u;
+    const uint32_t n = FULL ? 4u : (e0 >= t.count) ? 0u : (t.count - e0 < 4u) ? t.count - e0 : 4u;
+    const float4 z = row_ld<0, FULL>(a.z + t.aoff, e0, n);         // shared by the K waves: cacheable
+    for (uint32_t p = 0; p < passes; ++p) {
+        ReplicaTile<BF16> q[R];
+        float4 x[R], v[R], g[R], ss[R];
+        uint32_t kw[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            kw[r] = w + (p * R + (uint32_t)r) * W;
+            q[r] = replica_tile<BF16>(a, t, kw[r] < a.K ? kw[r] : a.K - 1u);
+            g[r] = row_ld_grad<BF16, NT, FULL>(q[r].g, e0, n);
+            x[r] = row_ld<NT, FULL>(q[r].xf, e0, n);
+            v[r] = row_ld<NT, FULL>(q[r].v, e0, n);
+            ss[r] = row_ld<NT, FULL>(q[r].s, e0, n);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            LASGD_FOR4(step_elem(comp(x[r], c), comp(v[r], c), compv(g[r], c), t.wd, a.mu, a.neg_lr, a.nesterov);)
+            LASGD_FOR4(comp(x[r], c) = merge_elem(compv(x[r], c), compv(ss[r], c), compv(z, c));)
+            if (kw[r] < a.K) {
+                row_st<NT, FULL>(q[r].v, e0, n, v[r]);
+                row_st<NT, FULL>(q[r].xf, e0, n, x[r]);
+                if constexpr (BF16) row_st16<NT, FULL>(q[r].x16, e0, n, x[r]);
+                row_st<NT, FULL>(q[r].s, e0, n, x[r]);
+                *reinterpret_cast<float4 *>(lds + (size_t)kw[r] * 256u + lane * 4u) = x[r];
+            }
+        }
+    }
+    __syncthreads();
+    // up to four waves finish the row's mean, one element per thread and turn
+    const uint32_t fin = (W < 4u ? W : 4u) * 64u;
+    if (threadIdx.x < fin) {
+        for (uint32_t c = threadIdx.x; c < 256u; c += fin) {
+            const uint32_t e = row * 256u + c;
+            if (FULL || e < t.count) {
+                double acc = 0.0;
+                for (uint32_t k = 0; k < a.K; ++k) acc += (double)lds[(size_t)k * 256u + c];
+                a.z[t.aoff + e] = group_mean_of(acc, a);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+template <int R, bool BF16, int NT>
+__global__ __launch_bounds__(1024) void step_merge_mean_kernel(const ApplyArgs a, const uint32_t passes)
+{
+    extern __shared__ float lds[];                        // [K][256]
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t W = blockDim.x >> 6;
+    for (uint32_t tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+        const Tile t = load_tile(a.tiles + tile);
+        const uint32_t rows = (t.count + 255u) >> 8;
+        for (uint32_t row = 0; row < rows; ++row) {
+            if (t.count - row * 256u >= 256u) step_merge_mean_row<R, BF16, NT, true>(a, t, lds, row, w, W, passes, lane);
+            else step_merge_mean_row<R, BF16, NT, false>(a, t, lds, row, w, W, passes, lane);
+        }
+    }
+}
+
+// Debugging aid for the two-stream protocol: fill z with NaN.
+__global__ __launch_bounds__(256) void poison_kernel(float *z, uint64_t n)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) z[i] = __uint_as_float(0x7fc00000u);
 }
 
 // ---- context-free global update on flat fp32 vectors -------------------------

@@ -105,10 +105,15 @@ class DeviceReplicas:
         self.ctx.snapshot()          # step 4: send
         self.ctx.average()           #         the All-Reduce starts on the side stream
 
-    def iteration(self, lr: float, tau: int, m: int, fused: bool = True) -> int:
-        """Steps 6-9 for one tick of the local clock; returns the new tau."""
+    def iteration(self, lr: float, tau: int, m: int, fused: bool = True, fused_mean: bool = False) -> int:
+        """Steps 6-9 for one tick of the local clock; returns the new tau.
+        fused_mean: the global update and the next All-Reduce go out as one pass on the
+        main stream (lasgd_step_merge_average) instead of step_merge + average."""
         tau += 1
         if tau == m:
+            if fused_mean:
+                self.ctx.step_merge_average(lr)
+                return 0
             if fused:
                 self.ctx.step_merge(lr, True)
             else:

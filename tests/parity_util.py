@@ -77,7 +77,7 @@ def compare_state(dev, orc: O32.Oracle, step: int, z_exact: bool = True, z_valid
 
 def run_parity(w: W.Workload, weight_decay: Optional[Sequence[float]] = None, fused: bool = True,
                tuning: Optional[dict] = None, side_stream: bool = True, z_exact: bool = True,
-               every_step: bool = True) -> int:
+               every_step: bool = True, fused_mean: bool = False) -> int:
     """Prologue + w.T iterations on both sides; compare after every step."""
     from paper_2203_13085_amd.driver import DeviceReplicas
     wd = list(weight_decay) if weight_decay is not None else [w.weight_decay] * len(w.numels)
@@ -89,7 +89,7 @@ def run_parity(w: W.Workload, weight_decay: Optional[Sequence[float]] = None, fu
         if tuning:
             dev.ctx.set_tuning(**tuning)
         say(f"[parity] {w.name} K={w.K} N={w.N} tensors={len(w.numels)} storage={w.storage} "
-            f"fused={fused} nesterov={w.nesterov} tuning={dev.ctx.get_tuning()}")
+            f"fused={fused} fused_mean={fused_mean} nesterov={w.nesterov} tuning={dev.ctx.get_tuning()}")
         orc.set_model(x0)
         dev.load_model(x0)
         g = grads(0)
@@ -102,7 +102,7 @@ def run_parity(w: W.Workload, weight_decay: Optional[Sequence[float]] = None, fu
             g = grads(i)
             orc.iteration(g, w.lr, w.m)
             dev.load_grads(g)
-            tau = dev.iteration(w.lr, tau, w.m, fused=fused)
+            tau = dev.iteration(w.lr, tau, w.m, fused=fused, fused_mean=fused_mean)
             if every_step or i == w.T:
                 zdiff += compare_state(dev, orc, i, z_exact)
         say(f"[parity] {w.name} done, z bit differences: {zdiff}")
