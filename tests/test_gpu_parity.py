@@ -84,10 +84,14 @@ def test_split_mean_staged_through_lds(K, split):
 
 # ---- bf16 storage -----------------------------------------------------------------
 @pytest.mark.parametrize("fused", [True, False])
-def test_bf16_storage(fused):
-    w = W.small(K=4, storage="bf16", m=2, T=6)
+@pytest.mark.parametrize("vec", [1, 2, 4])
+def test_bf16_storage(fused, vec):
+    # vec 2 and 4: tiles of 512 / 1024 elements, a lane owns 8 consecutive elements of each full
+    # 512-element row (128-bit accesses on the bf16 arrays); the sizes below give full tiles,
+    # tiles that end inside a row and inside a lane's 8 elements, and tensors smaller than a row
+    w = W.small(K=4, numels=(5, 1024, 1, 4099, 260, 64, 2048 + 517, 512), storage="bf16", m=2, T=6)
     wd = [1e-4 if i % 2 else 0.0 for i in range(len(w.numels))]
-    run_parity(w, weight_decay=wd, fused=fused)
+    run_parity(w, weight_decay=wd, fused=fused, tuning=dict(vec=vec))
 
 
 def test_bf16_storage_vec4_k32():
