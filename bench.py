@@ -35,40 +35,59 @@ def algorithmic_bytes(K: int, N: int, bf16: bool) -> dict:
     # fused step + global update + re-send: also read s and z (once per parameter), write s
     step_merge = step + 8 * K * N + 4 * N
     average = 4 * (K + 1) * N
-    return {"local_step": step, "step_merge": step_merge, "average": average}
+    # the same with the next mean computed in the pass: z is read once and written once per parameter
+    step_merge_average = step + 8 * K * N + 8 * N
+    return {"local_step": step, "step_merge": step_merge, "average": average, "step_merge_average": step_merge_average}
 
 
-def cpu_baseline(w, seconds: float = 12.0) -> dict:
-    """The oracle as it stands, timed on this machine's host cores on whole cycles of
-    the same workload (same shapes, K, cadence; one seeded gradient set reused)."""
+def cpu_baseline(w, seconds: float = 10.0) -> dict:
+    """The oracle as it stands, timed on this machine's host cores on whole cycles of the same
+    workload (same shapes, K, cadence; one seeded gradient set reused), twice in this same
+    run: the replica loop spread over all the cores it can use, and on a single thread.
+    The top-level value is the all-cores leg."""
     import numpy as np
     from oracle import lasgd_oracle as O32
     from paper_2203_13085_amd import workloads as W
-    threads = max(1, min(w.K, len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "64"))))
+    avail = len(os.sched_getaffinity(0))
+    many = max(1, min(w.K, avail, int(os.environ.get("OMP_NUM_THREADS", "64"))))
     nt = len(w.numels)
     x0 = np.concatenate([W.initial_tensor(w, t) for t in range(nt)])
     r = np.random.Generator(np.random.Philox(key=12345))
     g = [(r.standard_normal(w.N, dtype=np.float32) * np.float32(1e-3)) for _ in range(w.K)]
-    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, [w.weight_decay] * nt, threads=threads)
-    o.set_model(x0)
-    o.prologue(g, w.lr)
+    if w.storage == "bf16":
+        x0 = W.to_bf16_bits(x0)
+        g = [W.to_bf16_bits(a) for a in g]
 
-    def cycle():
-        for _ in range(w.m):
-            o.iteration(g, w.lr, w.m)
+    def leg(threads: int) -> dict:
+        o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, [w.weight_decay] * nt, storage=w.storage, threads=threads)
+        o.set_model(x0)
+        o.prologue(g, w.lr)
 
-    t0 = time.perf_counter()
-    cycle()
-    first = time.perf_counter() - t0
-    n = int(max(1, min(20, seconds / max(first, 1e-3))))
-    t0 = time.perf_counter()
-    for _ in range(n):
+        def cycle():
+            for _ in range(w.m):
+                o.iteration(g, w.lr, w.m)
+
+        t0 = time.perf_counter()
         cycle()
-    dt = time.perf_counter() - t0
-    return {"value": w.K * w.N * w.m * n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n} full cycles (m={w.m} local steps + global update + mean) of {w.name}, "
-                      f"all K={w.K} replicas and all {w.N} parameters, after one untimed cycle",
-            "ms_per_cycle": 1e3 * dt / n}
+        first = time.perf_counter() - t0
+        warm = "after one untimed cycle"
+        if first >= 0.6 * seconds:          # a cycle this long is its own sample
+            n, dt, warm = 1, first, "no warm-up"
+        else:
+            n = int(max(1, min(20, seconds / max(first, 1e-3))))
+            t0 = time.perf_counter()
+            for _ in range(n):
+                cycle()
+            dt = time.perf_counter() - t0
+        return {"value": w.K * w.N * w.m * n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
+                "sample": f"{n} full cycle(s) (m={w.m} local steps + global update + mean) of {w.name}, "
+                          f"all K={w.K} replicas and all {w.N} parameters, {warm}",
+                "ms_per_cycle": 1e3 * dt / n}
+
+    out = leg(many)
+    out["host_cores_available"] = avail
+    out["single_thread"] = leg(1) if many > 1 else dict(out)
+    return out
 
 
 def run_variant(args, w, make, alg) -> dict:
@@ -237,66 +256,69 @@ def main() -> int:
         print(json.dumps(run_variant(args, w, make, alg)), flush=True)
         return 0
 
-    # ---------------- the timed region: whole cycles; the mean runs on a second stream where
-    # the workload says so (the ResNet-50 configurations), else on the main stream ----------------
+    # ---------------- the timed region: whole cycles, issued exactly as a caller would issue them
+    # (no events, no host work between launches); the mean runs on a second stream where the
+    # workload says so (the ResNet-50 configurations), else on the main stream ----------------
     dev = make(side=w.side_stream)
     dev.prologue(w.lr)
     for _ in range(args.warmup):
         cycle(dev)
     dev.ctx.sync()
     torch.cuda.synchronize()
-    ev = {"local_step": [], "step_merge": [], "average": []}
-
-    def timed_cycle():
-        tau = 0
-        for _ in range(w.m):
-            tau += 1
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            if tau == w.m:
-                a.record(dev.main)
-                dev.ctx.step_merge(w.lr, True)
-                b.record(dev.main)
-                ev["step_merge"].append((a, b))
-                c, d = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                # the mean runs on the side stream once the main stream's work so far is done
-                if dev.side is not dev.main:
-                    dev.side.wait_stream(dev.main)
-                c.record(dev.side)
-                dev.ctx.average()
-                d.record(dev.side)
-                ev["average"].append((c, d))
-                tau = 0
-            else:
-                a.record(dev.main)
-                dev.ctx.local_step(w.lr)
-                b.record(dev.main)
-                ev["local_step"].append((a, b))
-
-    # events go around every launch of every fourth cycle (each pair costs a little host and
-    # queue time; the other cycles run exactly as a caller would issue them)
     t0 = time.perf_counter()
-    avg_end = {}                 # cycle index -> event after that cycle's mean (side stream)
-    for i in range(args.steps):
-        if i % 4 == 0:
-            timed_cycle()
-            ev["step_merge"][-1] += (i,)
-        else:
-            cycle(dev)
-            if i % 4 == 3:       # the mean the next instrumented step_merge will wait for
-                e = torch.cuda.Event(enable_timing=True)
-                e.record(dev.side)
-                avg_end[i] = e
+    for _ in range(args.steps):
+        cycle(dev)
     dev.ctx.sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     value = w.K * w.N * w.m * args.steps / dt
+
+    # ---------------- the same loop again with a HIP event pair around every launch, each on the
+    # stream its kernel runs on: per-kernel launch durations inside the pipelined run, and how long
+    # the main stream stood ready for a global update before the mean it needs had ended ----------
+    ev = {"local_step": [], "step_merge": [], "average": []}
+    ready, mean_end = [], []
+
+    def instrumented_cycle():
+        for _ in range(w.m - 1):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(dev.main)
+            dev.ctx.local_step(w.lr)
+            b.record(dev.main)
+            ev["local_step"].append((a, b))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(dev.main)
+        dev.ctx.step_merge(w.lr, True)
+        b.record(dev.main)
+        ev["step_merge"].append((a, b))
+        ready.append(a)
+        c, d = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if dev.side is not dev.main:
+            dev.side.wait_stream(dev.main)       # so that c marks the start of the mean, not of its wait
+        c.record(dev.side)
+        dev.ctx.average()
+        d.record(dev.side)
+        ev["average"].append((c, d))
+        mean_end.append(d)
+
+    n_inst = max(4, min(args.steps, 100))
+    t0 = time.perf_counter()
+    for _ in range(n_inst):
+        instrumented_cycle()
+    dev.ctx.sync()
+    torch.cuda.synchronize()
+    ms_instrumented = 1e3 * (time.perf_counter() - t0) / n_inst
     kern_ms = {k: float(np.mean([p[0].elapsed_time(p[1]) for p in v])) for k, v in ev.items() if v}
+    # > 0: the mean of cycle i-1 ended that long AFTER the main stream was ready for cycle i's global update
+    gaps = [ready[i].elapsed_time(mean_end[i - 1]) for i in range(1, len(ready))]
+    wait = float(np.mean([max(0.0, g) for g in gaps])) if gaps else 0.0
+    slack = float(np.mean(gaps)) if gaps else 0.0
     tuning = dev.ctx.get_tuning()
 
     detail = {}
     if not args.no_detail:
-        # ---- each kernel alone (nothing else on the GPU), and the serial (one-stream) cycle ----
+        # ---- each kernel alone (nothing else on the GPU) ----
         def alone(fn, n=30):
             dev.ctx.sync(); torch.cuda.synchronize()
             ts = []
@@ -327,19 +349,34 @@ def main() -> int:
             a.record(dev.side); dev.ctx.average(); b.record(dev.side)
 
         t_av = alone(f_av)
+
+        def f_sma(a, b):
+            dev.ctx.sync()
+            a.record(dev.main); dev.ctx.step_merge_average(w.lr); b.record(dev.main)
+
+        t_sma = alone(f_sma)
         dev.close()
         del dev
         torch.cuda.empty_cache()
-        def wall(two: bool) -> float:
+
+        # ---- whole cycles, wall clock: two streams, one stream, one stream with the global update and
+        # the next mean fused into one pass (lasgd_step_merge_average), and a HIP-graph replay ----
+        def wall(two: bool, fused_mean: bool = False) -> float:
             d = make(side=two)
             d.prologue(w.lr)
+
+            def cyc():
+                tau = 0
+                for _ in range(w.m):
+                    tau = d.iteration(w.lr, tau, w.m, fused_mean=fused_mean)
+
             for _ in range(args.warmup):
-                cycle(d)
+                cyc()
             d.ctx.sync(); torch.cuda.synchronize()
             n = max(10, args.steps // 4)
             t0 = time.perf_counter()
             for _ in range(n):
-                cycle(d)
+                cyc()
             d.ctx.sync(); torch.cuda.synchronize()
             out = 1e3 * (time.perf_counter() - t0) / n
             d.close()
@@ -348,22 +385,10 @@ def main() -> int:
             return out
 
         ms_two = wall(True)
-        ser = make(side=False)
-        ser.prologue(w.lr)
-        for _ in range(args.warmup):
-            cycle(ser)
-        ser.ctx.sync(); torch.cuda.synchronize()
+        ms_serial = wall(False)
+        ms_fused_mean = wall(False, fused_mean=True)
         ns = max(10, args.steps // 4)
-        t0 = time.perf_counter()
-        for _ in range(ns):
-            cycle(ser)
-        ser.ctx.sync(); torch.cuda.synchronize()
-        ms_serial = 1e3 * (time.perf_counter() - t0) / ns
-        # ---- the same cycle recorded once as a HIP graph and replayed (no per-launch host work) ----
-        ser.close()
-        del ser
-        torch.cuda.empty_cache()
-        gr = ser = make(side=True)
+        gr = make(side=True)
         gr.prologue(w.lr)
         gr.ctx.step_merge(w.lr, True)            # close the open cycle: models sent, no mean pending
         graph = gr.capture_cycle(w.lr, w.m)
@@ -378,34 +403,45 @@ def main() -> int:
         gr.ctx.sync(); torch.cuda.synchronize()
         ms_graph = 1e3 * (time.perf_counter() - t0) / ns
         del graph
-        ser.close()
-        # time the main stream lost waiting for the mean: how long after the main stream
-        # was ready for a step_merge (event before it) the previous mean ended (event after
-        # it on the side stream); negative = the mean was done long before, no wait
-        gaps = [p[0].elapsed_time(avg_end[p[2] - 1]) for p in ev["step_merge"] if p[2] - 1 in avg_end]
-        wait = float(np.mean([max(0.0, g) for g in gaps])) if gaps else 0.0
-        slack = float(np.mean(gaps)) if gaps else 0.0
+        gr.close()
+        fused_bytes = (w.m - 1) * alg["local_step"] + alg["step_merge_average"]
         detail = {
-            "alone_ms": {"local_step": t_step, "step_merge": t_sm, "average": t_av},
+            "alone_ms": {"local_step": t_step, "step_merge": t_sm, "average": t_av, "step_merge_average": t_sma},
             "alone_GBps": {"local_step": alg["local_step"] / t_step / 1e6, "step_merge": alg["step_merge"] / t_sm / 1e6,
-                           "average": alg["average"] / t_av / 1e6},
+                           "average": alg["average"] / t_av / 1e6,
+                           "step_merge_average": alg["step_merge_average"] / t_sma / 1e6},
             "ms_per_cycle_one_stream": ms_serial,
             "ms_per_cycle_two_streams": ms_two,
             "ms_per_cycle_hip_graph": ms_graph,
-            "overlap": None if not w.side_stream else {"T_avg_alone_ms": t_av, "T_avg_overlapped_ms": kern_ms["average"], "T_wait_ms": wait,
-                        "mean_ended_before_merge_by_ms": -slack, "hidden_frac": 1.0 - min(1.0, wait / t_av),
-                        "contention_cost": (ms_per_step - (ms_serial - t_av)) / t_av},
+            "fused_mean_cycle": {"what": "m-1 local_step + 1 lasgd_step_merge_average on one stream: the sent models are "
+                                         "not read back for the mean",
+                                 "ms_per_cycle": ms_fused_mean, "algorithmic_bytes": fused_bytes,
+                                 "GBps_algorithmic": fused_bytes / ms_fused_mean / 1e6,
+                                 "params_per_s": w.K * w.N * w.m / ms_fused_mean * 1e3,
+                                 "speedup_vs_one_stream": ms_serial / ms_fused_mean},
+            "overlap": None if not w.side_stream else {
+                "T_avg_alone_ms": t_av, "T_avg_overlapped_ms": kern_ms["average"], "T_wait_ms": wait,
+                "mean_ended_before_merge_by_ms": -slack,
+                # share of the mean's stand-alone time during which the main stream did not wait for it
+                "hidden_frac": 1.0 - min(1.0, wait / t_av),
+                # what the overlap buys in cycle time, in units of the mean's stand-alone time (both kernels
+                # are HBM-bound on one GPU, so this stays near 0: the bytes are moved either way)
+                "time_saved_frac": (ms_serial - ms_two) / t_av,
+                "contention_cost": (ms_two - (ms_serial - t_av)) / t_av},
         }
     else:
         dev.close()
 
     dom = "local_step" if (w.m - 1) * kern_ms.get("local_step", 0.0) >= kern_ms["step_merge"] else "step_merge"
     achieved = alg[dom] / kern_ms[dom] / 1e6          # bytes / ms -> GB/s
-    traffic = None
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(w.name, {}).get(dom)
+            rec = json.load(open(tpath))
+            traffic = rec.get(w.name, {}).get(dom)
+            if traffic is not None:
+                traffic_source = rec.get("_source")
         except Exception:
             traffic = None
     out = {
@@ -422,10 +458,14 @@ def main() -> int:
         "cycle_GBps_algorithmic": cycle_bytes / ms_per_step / 1e6,
         "cycle_frac_of_peak": cycle_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": kern_ms[dom]},
-        "kernels_in_timed_region": {k: {"avg_ms": v, "GBps": alg[k] / v / 1e6, "frac": alg[k] / v / 1e6 / HBM_PEAK_GBS,
-                                        "launches": len(ev[k])} for k, v in kern_ms.items()},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": kern_ms[dom],
+                     "timing": f"HIP events on the kernel's own stream around every launch of {n_inst} cycles issued "
+                               f"right after the timed region, same pipelined pattern ({ms_instrumented:.4f} ms per "
+                               f"cycle with the events, {ms_per_step:.4f} without)"},
+        "kernels_in_instrumented_repeat": {k: {"avg_ms": v, "GBps": alg[k] / v / 1e6, "frac": alg[k] / v / 1e6 / HBM_PEAK_GBS,
+                                               "launches": len(ev[k])} for k, v in kern_ms.items()},
+        "ms_per_cycle_instrumented": ms_instrumented,
     }
     out.update(detail)
     if not args.no_cpu_baseline:

@@ -244,18 +244,23 @@ lasgd_status plan_apply(lasgd_ctx *c, ApplyPlan &p, int op, float lr, int resnap
     if (kper > c->K) kper = c->K;
     a.kper = (uint32_t)kper;
     a.kgroups = (uint32_t)((c->K + kper - 1) / kper);
-    const uint64_t nitems = (uint64_t)a.ntiles * a.kgroups;
-    if (nitems == 0 || nitems > 0x7fffffffull) return fail(c, LASGD_ERR_UNSUPPORTED, "work-item count %llu out of range", (unsigned long long)nitems);
-    a.nitems = (uint32_t)nitems;
     a.neg_lr = -lr;
     a.resnap = resnap;
-    int64_t chunk = (op == OP_MERGE || op == OP_STEP_MERGE) ? c->tune.chunk_merge : c->tune.chunk_step;
-    if (chunk < 1 || chunk > (int64_t)a.ntiles) chunk = a.ntiles;          // whole replica
-    a.chunk = (uint32_t)chunk;
-    const uint32_t nfull = a.ntiles / a.chunk;
+    const bool merging = op == OP_MERGE || op == OP_STEP_MERGE;
+    int64_t chunk = merging ? c->tune.chunk_merge : c->tune.chunk_step;
+    if (chunk < 1 || chunk > (int64_t)a.ntiles) chunk = merging ? 0 : a.ntiles;   // 0: one chunk, handled as the tail
+    a.chunk = chunk ? (uint32_t)chunk : 1u;
+    const uint32_t nfull = chunk ? a.ntiles / a.chunk : 0u;
     a.full_items = nfull * a.chunk * a.kgroups;
     a.tail_first = nfull * a.chunk;
-    a.tail_chunk = a.ntiles - a.tail_first ? a.ntiles - a.tail_first : 1u;
+    const uint32_t tail = a.ntiles - a.tail_first;
+    a.tail_chunk = tail ? tail : 1u;
+    // passes over the shared z should start on the same XCD for every replica group: 8 XCDs x up to 4 waves
+    // per workgroup.  A local step or snapshot reads no z and keeps its items dense.
+    a.tail_stride = merging ? (uint32_t)round_up(a.tail_chunk, 32) : a.tail_chunk;
+    const uint64_t nitems = (uint64_t)a.full_items + (tail ? (uint64_t)a.tail_stride * a.kgroups : 0u);
+    if (nitems == 0 || nitems > 0x7fffffffull) return fail(c, LASGD_ERR_UNSUPPORTED, "work-item count %llu out of range", (unsigned long long)nitems);
+    a.nitems = (uint32_t)nitems;
     const uint32_t wpb = (uint32_t)c->tune.waves_per_block;
     uint64_t blocks = (nitems + wpb - 1) / wpb;
     if (c->tune.max_blocks > 0 && blocks > (uint64_t)c->tune.max_blocks) blocks = (uint64_t)c->tune.max_blocks;

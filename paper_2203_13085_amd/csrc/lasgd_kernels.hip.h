@@ -58,6 +58,8 @@ struct ApplyArgs {
     uint32_t full_items;    // (ntiles / chunk) * chunk * kgroups
     uint32_t tail_first;    // first tile of the last, shorter chunk
     uint32_t tail_chunk;    // its length (>= 1 even when unused)
+    uint32_t tail_stride;   // items per replica group in the last chunk: tail_chunk rounded up so that every
+                            // group's pass starts on the same XCD; the items in between do nothing
     // the replica-group kernels finish a mean over all K replicas themselves
     int32_t use_mul;        // K is a power of two: multiply by the exact reciprocal
     double inv_k, k_as_double;
@@ -287,7 +289,8 @@ __device__ __forceinline__ void apply_body(const ApplyArgs &a, const ExtArgs *xa
         // chunk = ntiles: one replica after the other).  Workgroups go to the eight
         // XCDs round-robin, each with its own L2: when a chunk is a multiple of eight
         // workgroups long, tile j of every replica lands on the same XCD, so only the
-        // first replica's request for a z tile misses that L2.
+        // first replica's request for a z tile misses that L2.  The last, shorter chunk is
+        // padded with idle items to such a multiple for the same reason.
         uint32_t tile, kg;
         if (item < a.full_items) {
             const uint32_t per = a.chunk * a.kgroups;
@@ -297,8 +300,10 @@ __device__ __forceinline__ void apply_body(const ApplyArgs &a, const ExtArgs *xa
             tile = ch * a.chunk + (r - kg * a.chunk);
         } else {
             const uint32_t r = item - a.full_items;
-            kg = r / a.tail_chunk;
-            tile = a.tail_first + (r - kg * a.tail_chunk);
+            kg = r / a.tail_stride;
+            const uint32_t i = r - kg * a.tail_stride;
+            if (i >= a.tail_chunk) continue;                    // padding item
+            tile = a.tail_first + i;
         }
         const Tile t = load_tile(a.tiles + tile);
         const bool full = (t.count == 256u * VEC);
