@@ -11,7 +11,11 @@ parameters each, global update every m = 4 local steps):
 
 i.e. m local updates of all K replicas plus one global update.  All inputs are
 synthetic, seeded and already resident in HBM when the timed region starts.
-Prints ONE JSON line.
+The timed loop issues the calls exactly as a caller would (no events, no host
+work in between); per-kernel launch durations for the roofline come from an
+instrumented repeat of the same loop, stand-alone kernel times, the one-stream
+and fused-mean cycles and the CPU oracle (all cores, one thread) from further
+legs of the same run.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
