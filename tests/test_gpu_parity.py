@@ -270,6 +270,10 @@ def test_graph_replay_equals_eager(m):
         o.local_step(g, w.lr); o.snapshot()
         dev.ctx.local_step(w.lr); dev.ctx.snapshot()
         graph = dev.capture_cycle(w.lr, m)        # capturing does not execute
+        # the mean was recorded, not launched: there is nothing this call could poll
+        with pytest.raises(B.LasgdError) as e:
+            dev.ctx.average_done()
+        assert e.value.status == B.ERR_STATE
 
         def oracle_cycle():
             o.average()
@@ -294,6 +298,7 @@ def test_graph_replay_equals_eager(m):
                 dev.ctx.step_merge(w.lr, True)
                 oracle_cycle()
                 dev.ctx.sync()
+                assert dev.ctx.average_done()        # an eager mean can be polled again
         # two replays back to back without host synchronisation
         with torch.cuda.stream(dev.main):
             graph.replay()
