@@ -5,7 +5,10 @@
  * the state after every step with the CPU oracle (test infrastructure, linked
  * as a separate shared library), bit for bit.
  *
- * Usage: abi_check [K] [m] [T]      exit status 0 = all steps identical.
+ * Usage: abi_check [K] [m] [T] [fused]      exit status 0 = all steps identical.
+ * fused = 1: the global update and the next All-Reduce go out as one call,
+ * lasgd_step_merge_average.  At the end the context-free, allocation-free
+ * lasgd_global_update_static is checked on copies of the final state.
  */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
@@ -41,6 +44,7 @@ static const float wd[NT] = {1e-4f, 0.0f, 1e-3f, 0.0f};
 int main(int argc, char **argv)
 {
     const int K = argc > 1 ? atoi(argv[1]) : 3, m = argc > 2 ? atoi(argv[2]) : 2, T = argc > 3 ? atoi(argv[3]) : 6;
+    const int fused = argc > 4 ? atoi(argv[4]) : 0;
     const float lr = 0.05f, mu = 0.9f;
     int64_t N = 0, off[NT + 1];
     for (int t = 0; t < NT; ++t) { off[t] = N; N += numel[t]; }
@@ -99,6 +103,7 @@ int main(int argc, char **argv)
         if (fire) lasgd_oracle_average(oz, (const float *const *)os, K, N);
         /* library */
         if (step == 0) { LASGD(lasgd_local_step(ctx, lr)); LASGD(lasgd_snapshot(ctx)); LASGD(lasgd_average(ctx)); }
+        else if (fire && fused) LASGD(lasgd_step_merge_average(ctx, lr));
         else if (fire) { LASGD(lasgd_step_merge(ctx, lr, 1)); LASGD(lasgd_average(ctx)); }
         else LASGD(lasgd_local_step(ctx, lr));
         /* compare */
@@ -115,8 +120,37 @@ int main(int argc, char **argv)
     }
     int32_t done = 0;
     LASGD(lasgd_average_done(ctx, &done));
+
+    /* the allocation-free global update on flat copies of the final models: pretend every replica made
+     * one more bit of progress (x != s) and compare with the oracle's mean + global update */
+    {
+        float **fx = calloc(K, sizeof *fx), **fs = calloc(K, sizeof *fs);
+        for (int k = 0; k < K; ++k) {
+            for (int64_t e = 0; e < N; ++e) ox[k][e] += draw(3, 0, k, e, 1e-3f);
+            HIP(hipMalloc((void **)&fx[k], N * sizeof(float)));
+            HIP(hipMalloc((void **)&fs[k], N * sizeof(float)));
+            HIP(hipMemcpy(fx[k], ox[k], N * sizeof(float), hipMemcpyHostToDevice));
+            HIP(hipMemcpy(fs[k], os[k], N * sizeof(float), hipMemcpyHostToDevice));
+        }
+        lasgd_status gs = lasgd_global_update_static(K, N, fx, fs, 1, main_s);
+        if (gs != LASGD_OK) { fprintf(stderr, "lasgd_global_update_static -> %d: %s\n", (int)gs, lasgd_last_error(NULL)); return 3; }
+        HIP(hipStreamSynchronize(main_s));
+        lasgd_oracle_average(oz, (const float *const *)os, K, N);
+        for (int k = 0; k < K; ++k) lasgd_oracle_merge_f32(ox[k], os[k], oz, N, 1);
+        for (int k = 0; k < K; ++k)
+            for (int pass = 0; pass < 2; ++pass) {
+                HIP(hipMemcpy(tmp, pass ? fs[k] : fx[k], N * sizeof(float), hipMemcpyDeviceToHost));
+                const float *ref = pass ? os[k] : ox[k];
+                for (int64_t e = 0; e < N; ++e)
+                    if (memcmp(&tmp[e], &ref[e], 4) != 0 && !(tmp[e] == 0.0f && ref[e] == 0.0f)) {
+                        if (bad < 5) fprintf(stderr, "static update, %s replica %d element %lld: %.9g vs %.9g\n", pass ? "sent" : "x", k, (long long)e, tmp[e], ref[e]);
+                        ++bad;
+                    }
+            }
+        for (int k = 0; k < K; ++k) { (void)hipFree(fx[k]); (void)hipFree(fs[k]); }
+    }
     lasgd_destroy(ctx);
     for (int k = 0; k < K; ++k) { (void)hipFree(dx[k]); (void)hipFree(dg[k]); }
-    printf("abi_check K=%d m=%d T=%d N=%lld: %s (%d mismatching values)\n", K, m, T, (long long)N, bad ? "FAIL" : "PASS", bad);
+    printf("abi_check K=%d m=%d T=%d fused=%d N=%lld: %s (%d mismatching values)\n", K, m, T, fused, (long long)N, bad ? "FAIL" : "PASS", bad);
     return bad ? 4 : 0;
 }

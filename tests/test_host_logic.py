@@ -29,6 +29,16 @@ def test_library_exports_every_declared_symbol():
     assert sorted(B.EXPORTS) == names
 
 
+def test_library_is_built_from_the_current_sources():
+    """The tests and the GPU runs load the in-tree library as it is; one left over from an
+    experiment or an older source would be measured and tested instead of the code."""
+    lib = os.path.getmtime(B.LIB_PATH)
+    srcs = [os.path.join(ROOT, "paper_2203_13085_amd", "csrc", f) for f in os.listdir(os.path.join(ROOT, "paper_2203_13085_amd", "csrc"))]
+    srcs.append(os.path.join(ROOT, "include", "lasgd.h"))
+    stale = [os.path.relpath(f, ROOT) for f in srcs if os.path.getmtime(f) > lib]
+    assert not stale, f"rebuild the library (python __graft_entry__.py): newer than it are {stale}"
+
+
 def test_binding_struct_layouts_match_header():
     # field order and count of the two structs the binding mirrors
     text = open(os.path.join(ROOT, "include", "lasgd.h")).read()
