@@ -78,6 +78,31 @@ def test_static_global_update_two_calls_second_smaller():
     _one_call(K=3, n=4_098, resnapshot=False, seed=22)       # smaller; stale z beyond n must not matter
 
 
+def test_static_global_update_at_the_maximum_size():
+    """n = LASGD_STATIC_MAX_N exactly (the whole static buffer), K = 2, inputs drawn on the device."""
+    n, K = B.STATIC_MAX_N, 2
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(3)
+    xs = [torch.randn(n, generator=gen, device="cuda:0") * 0.01 for _ in range(K)]
+    ss = [x + torch.randn(n, generator=gen, device="cuda:0") * 1e-3 for x in xs]
+    hx = [t.cpu().numpy() for t in xs]
+    hs = [t.cpu().numpy() for t in ss]
+    say(f"[no-alloc] K={K} n={n} (maximum)")
+    B.global_update_static([t.data_ptr() for t in xs], [t.data_ptr() for t in ss], n, True)
+    torch.cuda.synchronize()
+    orc = O32.Oracle(K, [n], 0.9, True, [0.0], threads=2)
+    for k in range(K):
+        orc.x[k][:] = hx[k]
+        orc.s[k][:] = hs[k]
+    orc.average()
+    orc.merge(resnapshot=True)
+    for k in range(K):
+        np.testing.assert_array_equal(_bits(xs[k].cpu().numpy()), _bits(orc.x[k]), err_msg=f"x replica {k}")
+        np.testing.assert_array_equal(_bits(ss[k].cpu().numpy()), _bits(orc.s[k]), err_msg=f"sent replica {k}")
+    del xs, ss
+    torch.cuda.empty_cache()
+
+
 def test_static_global_update_refuses_bad_arguments():
     t = torch.zeros(64, device="cuda:0")
     u = torch.zeros(64, device="cuda:0")
