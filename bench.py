@@ -392,7 +392,7 @@ def main() -> int:
         ms_serial = wall(False)
         ms_fused_mean = wall(False, fused_mean=True)
         ns = max(10, args.steps // 4)
-        gr = make(side=True)
+        gr = make(side=w.side_stream)          # the graph forks to a second stream only where the workload does
         gr.prologue(w.lr)
         gr.ctx.step_merge(w.lr, True)            # close the open cycle: models sent, no mean pending
         graph = gr.capture_cycle(w.lr, w.m)
