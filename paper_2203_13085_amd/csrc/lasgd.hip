@@ -63,6 +63,7 @@ struct lasgd_ctx {
     uint64_t pending_mask = 0;   // participants of the launched mean that have not merged yet
     bool avg_ever = false;
     bool avg_in_graph = false;   // the last mean was recorded into a graph, not executed: evZ says nothing about it
+    bool z_on_main = false;      // the pending mean was enqueued on the main stream: stream order already puts it first
     bool center_valid = false;   // z has been computed at least once
     float alpha = 1.f, beta = 1.f;   // elastic coefficients (Sec. 3, Eq. 5-6); 1, 1 = Algorithm 1
 
@@ -659,6 +660,7 @@ static lasgd_status do_average(lasgd_ctx *c, uint64_t mask)
     c->avg_ever = true;
     c->center_valid = true;
     c->avg_in_graph = captured;
+    c->z_on_main = c->side == c->main;
     LASGD_HIP(c, hipEventRecord(c->evZ, c->side));
     return LASGD_OK;
 }
@@ -684,8 +686,8 @@ static lasgd_status do_merge(lasgd_ctx *c, int op, const float *lr_k, float lr, 
     if (plain) st = plan_apply(c, p, op, lr_k ? lr_k[0] : lr, resnapshot ? 1 : 0);
     else st = plan_apply(c, p, op, 0.f, resnapshot ? 1 : 0, &x);
     if (st != LASGD_OK) return st;
-    // nothing can be refused any more: now the main stream waits for z
-    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    // nothing can be refused any more: now the main stream waits for z (unless z is made on this very stream)
+    if (!c->z_on_main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
     st = launch_apply(c, p);
     if (st != LASGD_OK) return st;
     c->pending_mask &= ~merge_mask;
@@ -811,7 +813,7 @@ lasgd_status lasgd_step_merge_average(lasgd_ctx *c, float lr)
     a.resnap = 1;
     const GroupShape g = group_shape(c, 1);
     const bool captured = is_capturing(c->main);
-    if (c->side != c->main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
+    if (!c->z_on_main) LASGD_HIP(c, hipStreamWaitEvent(c->main, c->evZ, 0));
     hipError_t e = launch_group(1, a, g, c->main, c->storage == LASGD_BF16, c->tune.nontemporal);
     if (e != hipSuccess) return fail(c, LASGD_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     // every replica has merged and re-sent, and the mean of the sent models is (being) written to z
@@ -819,6 +821,7 @@ lasgd_status lasgd_step_merge_average(lasgd_ctx *c, float lr)
     c->snap_mask = c->all;
     c->pending_mask = c->all;
     c->avg_in_graph = captured;
+    c->z_on_main = true;
     LASGD_HIP(c, hipEventRecord(c->evZ, c->main));
     return LASGD_OK;
 }

@@ -158,5 +158,19 @@ class DeviceReplicas:
             self.ctx.step_merge(lr, True)
         return graph
 
+    def capture_fused_cycle(self, lr: float, m: int):
+        """Record m-1 local steps + lasgd_step_merge_average as a HIP graph on the main stream.
+        Call it when the pending mean was itself made by lasgd_step_merge_average (or with one
+        stream for everything): the graph then contains no wait on an event recorded outside it.
+        It starts and ends in the state "models sent, mean pending", so it replays back to back."""
+        graph = torch.cuda.CUDAGraph()
+        self.ctx.sync()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=self.main):
+            for _ in range(m - 1):
+                self.ctx.local_step(lr)
+            self.ctx.step_merge_average(lr)
+        return graph
+
     def close(self) -> None:
         self.ctx.close()

@@ -97,6 +97,64 @@ def test_fused_mean_mixes_with_the_two_stream_calls():
         dev.close()
 
 
+@pytest.mark.parametrize("m", [1, 3])
+def test_fused_mean_graph_replay_equals_eager(m):
+    """m-1 local steps + the fused call captured as one graph and replayed several times, with
+    eager library work and host synchronisation between the replays: every replay must give the
+    oracle's state (z included: the graph writes it in place)."""
+    import torch
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=4, numels=(70000, 5, 1024, 4099), m=m)
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    try:
+        g = grads(1)
+        o.set_model(x0); dev.load_model(x0); dev.load_grads(g)
+        o.prologue(g, w.lr); dev.prologue(w.lr)
+        # one eager cycle through the fused call: from here on z is made on the main stream
+        for _ in range(m):
+            o.iteration(g, w.lr, m)
+        for _ in range(m - 1):
+            dev.ctx.local_step(w.lr)
+        dev.ctx.step_merge_average(w.lr)
+        graph = dev.capture_fused_cycle(w.lr, m)
+        with pytest.raises(B.LasgdError) as e:           # recorded, not launched: nothing to poll
+            dev.ctx.average_done()
+        assert e.value.status == B.ERR_STATE
+        for rep in range(5):
+            with torch.cuda.stream(dev.main):
+                graph.replay()
+            for _ in range(m):
+                o.iteration(g, w.lr, m)
+            compare_state(dev, o, rep)
+            if rep % 2 == 0:                             # an eager cycle in between, two-stream calls
+                for _ in range(m - 1):
+                    dev.ctx.local_step(w.lr)
+                dev.ctx.step_merge(w.lr, True)
+                dev.ctx.average()
+                for _ in range(m):
+                    o.iteration(g, w.lr, m)
+                dev.ctx.sync()
+                assert dev.ctx.average_done()
+                # back to "z made on the main stream" before the next replay
+                for _ in range(m - 1):
+                    dev.ctx.local_step(w.lr)
+                dev.ctx.step_merge_average(w.lr)
+                for _ in range(m):
+                    o.iteration(g, w.lr, m)
+        with torch.cuda.stream(dev.main):                # back to back, no host synchronisation
+            graph.replay()
+            graph.replay()
+        for _ in range(2 * m):
+            o.iteration(g, w.lr, m)
+        compare_state(dev, o, 99)
+    finally:
+        dev.close()
+
+
 @pytest.mark.parametrize("storage,K", [("f32", 1), ("f32", 3), ("f32", 8), ("bf16", 16), ("f32", 17), ("bf16", 33),
                                        ("f32", 64)])
 def test_sgd_ar_every_group_shape(storage, K):
