@@ -275,7 +275,7 @@ lasgd_status lasgd_read_state(lasgd_ctx *ctx, int32_t which, int32_t k, int32_t 
  *     z = (1/K) sum_k sent[k]   (fp64 accumulation in replica order, one rounding)
  *     x[k] <- z + (x[k] - sent[k]);  resnapshot != 0: sent[k] <- x[k]
  * Same roundings as the context calls.  x, sent: host arrays [K] of device
- * pointers to n fp32 elements each, 16-byte aligned, all distinct; they are the
+ * pointers to n fp32 elements each, 16-byte aligned, no two overlapping; they are the
  * caller's, are read during the call (the arrays) and updated in place on the
  * device (the buffers).  stream: hipStream_t (NULL = default stream); both
  * kernels are enqueued on it, the call does not wait for them.  z is kept in a
@@ -284,7 +284,7 @@ lasgd_status lasgd_read_state(lasgd_ctx *ctx, int32_t which, int32_t k, int32_t 
  * call, so nothing needs clearing, and its contents are not an output.  All calls
  * on one GPU share that array: two calls whose kernels may overlap on the device
  * (different streams, no ordering) race.  Error text: lasgd_last_error(NULL).
- * Errors: INVALID (NULL, K outside 1..64, n < 1, NULL / misaligned / repeated
+ * Errors: INVALID (NULL, K outside 1..64, n < 1, NULL / misaligned / overlapping
  * buffer), UNSUPPORTED (n > LASGD_STATIC_MAX_N), HIP.  A failed call leaves the caller's
  * buffers untouched.
  */

@@ -992,12 +992,18 @@ extern "C" lasgd_status lasgd_global_update_static(int32_t K, int64_t n, float *
             if (!x[k] || !sent[k]) return fail(nullptr, LASGD_ERR_INVALID, "NULL buffer for replica %d", k);
             if (((uintptr_t)x[k] | (uintptr_t)sent[k]) & 15u)
                 return fail(nullptr, LASGD_ERR_INVALID, "buffer of replica %d is not 16-byte aligned", k);
-            for (int32_t j = 0; j < k; ++j)
-                if (x[k] == x[j] || sent[k] == sent[j] )
-                    return fail(nullptr, LASGD_ERR_INVALID, "replicas %d and %d share a buffer", j, k);
             a.x[k] = x[k];
             a.s[k] = sent[k];
         }
+        // the 2K buffers must not overlap: every one of them is written by one replica's waves only
+        const uintptr_t bytes = (uintptr_t)n * sizeof(float);
+        for (int32_t i = 0; i < 2 * K; ++i)
+            for (int32_t j = 0; j < i; ++j) {
+                const uintptr_t p = (uintptr_t)(i < K ? x[i] : sent[i - K]), q = (uintptr_t)(j < K ? x[j] : sent[j - K]);
+                if (p < q + bytes && q < p + bytes)
+                    return fail(nullptr, LASGD_ERR_INVALID, "%s of replica %d overlaps %s of replica %d",
+                                i < K ? "x" : "sent", i < K ? i : i - K, j < K ? "x" : "sent", j < K ? j : j - K);
+            }
         float *z = nullptr;
         lasgd_status st = scratch_for_current_device(&z);
         if (st != LASGD_OK) return st;

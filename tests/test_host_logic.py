@@ -100,7 +100,8 @@ def test_static_global_update_validates_before_any_device_call():
     """No GPU here: every refusal below must come back as a status, not a HIP error."""
     buf = (ctypes.c_void_p * 2)(0x1000, 0x2000)
     bad = (ctypes.c_void_p * 2)(0x1004, 0x2000)
-    same = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    same = (ctypes.c_void_p * 2)(0x1000, 0x1010)          # 16 bytes apart, 32 bytes long: they overlap
+    cross = (ctypes.c_void_p * 2)(0x2010, 0x3000)         # overlaps the second entry of buf
     L = B.load()
     assert L.lasgd_global_update_static(2, 8, None, buf, 1, None) == B.ERR_INVALID
     assert L.lasgd_global_update_static(0, 8, buf, buf, 1, None) == B.ERR_INVALID
@@ -108,6 +109,8 @@ def test_static_global_update_validates_before_any_device_call():
     assert L.lasgd_global_update_static(2, 0, buf, buf, 1, None) == B.ERR_INVALID
     assert L.lasgd_global_update_static(2, 8, bad, buf, 1, None) == B.ERR_INVALID
     assert L.lasgd_global_update_static(2, 8, same, buf, 1, None) == B.ERR_INVALID
+    assert L.lasgd_global_update_static(2, 8, buf, cross, 1, None) == B.ERR_INVALID
+    assert b"overlaps" in L.lasgd_last_error(None)
     assert L.lasgd_global_update_static(2, B.STATIC_MAX_N + 1, buf, same, 1, None) == B.ERR_UNSUPPORTED
     assert b"LASGD_STATIC_MAX_N" in L.lasgd_last_error(None)
     text = open(os.path.join(ROOT, "include", "lasgd.h")).read()
