@@ -258,11 +258,12 @@ def test_live_polling_replayed_through_the_oracle(tau_max):
         dev.close()
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(16))
 def test_random_legal_call_sequences(seed):
     """Randomly drawn, legal sequences of the extended calls (masked steps with
     per-replica step sizes, partial means, staggered partial merges with and
-    without re-sending, late snapshots, elastic coefficients): device and oracle
+    without re-sending, late snapshots, elastic coefficients, the fused
+    step + global update + next mean where it is legal): device and oracle
     must agree after every call group."""
     r = np.random.default_rng(500 + seed)
     K = int(r.integers(1, 9))
@@ -287,6 +288,13 @@ def test_random_legal_call_sequences(seed):
             lrs = [float(np.float32(v)) for v in r.uniform(0.01, 0.2, size=K)]
             mask = int(r.integers(0, full + 1))
             part = 0
+            if pending == full and alpha == 1.0 and beta == 1.0 and r.random() < 0.35:
+                # everybody steps, merges, re-sends and the next mean is taken in the same pass
+                orc.local_step(g, lrs[0]); orc.merge(True); orc.average()
+                c.step_merge_average(lrs[0])
+                sent = full
+                compare_state(dev, orc, step, z_exact=False)
+                continue
             if pending and r.random() < 0.6:
                 part = (int(r.integers(1, pending + 1)) & pending) or pending
                 resnap = bool(r.integers(0, 2))
