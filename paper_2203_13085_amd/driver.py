@@ -124,16 +124,20 @@ class DeviceReplicas:
         self.ctx.local_step(lr)
         return tau
 
-    def adaptive_iteration(self, lr: float, tau: int, tau_max: int) -> tuple:
+    def adaptive_iteration(self, lr: float, tau: int, tau_max: int, fused_mean: bool = False) -> tuple:
         """Steps 6-9 with the paper's adaptive rule: the global update fires as
         soon as the All-Reduce is found finished, or when tau reaches tau_max (then
         the main stream waits for it on the device; the host never blocks).  The
         poll happens before the step is enqueued so that step and global update
-        can go out as one fused pass.  Returns (new tau, fired)."""
+        can go out as one fused pass.  fused_mean: the next All-Reduce is taken in that
+        same pass (lasgd_step_merge_average).  Returns (new tau, fired)."""
         tau += 1
         if tau >= tau_max or self.ctx.average_done():
-            self.ctx.step_merge(lr, True)
-            self.ctx.average()
+            if fused_mean:
+                self.ctx.step_merge_average(lr)
+            else:
+                self.ctx.step_merge(lr, True)
+                self.ctx.average()
             return 0, True
         self.ctx.local_step(lr)
         return tau, False

@@ -225,7 +225,8 @@ def test_mask_order_rules():
 
 
 @pytest.mark.parametrize("tau_max", [1, 3, 5])
-def test_live_polling_replayed_through_the_oracle(tau_max):
+@pytest.mark.parametrize("fused_mean", [False, True])
+def test_live_polling_replayed_through_the_oracle(tau_max, fused_mean):
     """The real adaptive rule: poll "All Reduce done" on the device, cap at
     tau_max.  Which iterations fire depends on timing, so the decisions are
     recorded and replayed through the oracle; whatever they were, the states
@@ -239,13 +240,13 @@ def test_live_polling_replayed_through_the_oracle(tau_max):
         dev.prologue(w.lr)
         tau, fired_at, since = 0, [], 0
         for i in range(1, w.T + 1):
-            tau, fired = dev.adaptive_iteration(w.lr, tau, tau_max)
+            tau, fired = dev.adaptive_iteration(w.lr, tau, tau_max, fused_mean=fused_mean)
             since += 1
             if fired:
                 fired_at.append(i)
                 assert since <= tau_max
                 since = 0
-        say(f"[live] tau_max={tau_max}: global updates fired at iterations {fired_at}")
+        say(f"[live] tau_max={tau_max} fused_mean={fused_mean}: global updates fired at iterations {fired_at}")
         if tau_max == 1:
             assert fired_at == list(range(1, w.T + 1))
         for i in range(1, w.T + 1):
