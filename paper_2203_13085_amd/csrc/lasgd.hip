@@ -26,7 +26,9 @@ using namespace lasgd;
 namespace {
 
 constexpr int kMaxK = 64;
-constexpr uint64_t kArenaAlign = 64;                       // elements: every tensor starts on 256 B
+// Elements.  Every tensor starts on 1 KiB inside a replica's slab, so that each 256-element tile is one aligned
+// KiB: tiles that start 256 or 512 bytes off such a boundary stream 3-5 % slower on MI355X.
+constexpr uint64_t kArenaAlign = 256;
 constexpr uint64_t kMaxNpad = (1ull << 31) - (1ull << 20); // tile offsets stay far inside 32-bit element counts
 
 thread_local std::string g_create_error;
