@@ -38,7 +38,7 @@ class DeviceReplicas:
     """K replicas' parameters and gradients on the GPU, bound to a LASGD context."""
 
     def __init__(self, w: Workload, weight_decay: Optional[Sequence[float]] = None,
-                 side_stream: bool = True, device: str = "cuda:0"):
+                 side_stream: bool = True, device: str = "cuda:0", grad_lead_bytes: int = _GRAD_LEAD_BYTES):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the LASGD path runs only on the device")
         self.w = w
@@ -52,7 +52,7 @@ class DeviceReplicas:
         self.main = torch.cuda.Stream(device=self.dev)
         self.side = torch.cuda.Stream(device=self.dev) if side_stream else self.main
         total = int(self.off[-1])
-        lead = _GRAD_LEAD_BYTES // self.esize
+        lead = int(grad_lead_bytes) // self.esize
         self.x = [torch.zeros(total, dtype=dt, device=self.dev) for _ in range(w.K)]
         self._g_alloc = [torch.zeros(total + lead, dtype=dt, device=self.dev) for _ in range(w.K)]
         self.g = [t[lead:] for t in self._g_alloc]
