@@ -99,9 +99,12 @@ def _compare_everything(dev, orc, step, z_ties):
     return assert_same(dev.ctx.read_state(B.STATE_Z), orc.z, f"z step {step}", max_bit_diffs=z_ties)
 
 
-def _full_size_run(cfg, fused_mean=False, full_every_step=True, sample=None):
+def _full_size_run(cfg, fused_mean=False, full_every_step=True, sample=None, T=None):
+    import dataclasses
     from paper_2203_13085_amd.driver import DeviceReplicas
     w = W.config(cfg)
+    if T is not None:
+        w = dataclasses.replace(w, T=T)
     bf16 = w.storage == "bf16"
     nt = len(w.numels)
     wd = [w.weight_decay] * nt
@@ -163,6 +166,15 @@ def test_full_size_every_element_every_step(cfg):
 def test_full_size_fused_mean_every_element_every_step():
     # configs[3] (a global update every step) through lasgd_step_merge_average
     _full_size_run(3, fused_mean=True)
+
+
+def test_full_size_hundred_steps():
+    """configs[2] for 100 loop iterations (25 global updates) with a fresh gradient every step: a column sample
+    after every step, every element of every array after every global update.  Rounding differences would
+    have a hundred steps to surface and grow; there must be none."""
+    w = W.config(2)
+    cols, _ = _sample_columns(w.numels, np.random.default_rng(102), 60000)
+    _full_size_run(2, full_every_step=False, sample=cols, T=100)
 
 
 def test_full_size_bf16_k32():
