@@ -299,7 +299,9 @@ lasgd_status lasgd_global_update_static(int32_t K, int64_t n, float *const *x, f
 /* Wait until both streams have finished everything this context enqueued. */
 lasgd_status lasgd_sync(lasgd_ctx *ctx);
 
-/* Change launch-shape knobs (waits for enqueued work first).
+/* Change launch-shape knobs (waits for enqueued work first).  A graph captured
+ * earlier keeps the shape it was recorded with and stays valid (the tile table
+ * of every tile size used is kept until lasgd_destroy).
  * Errors: INVALID (NULL, a field outside its documented values), HIP, ALLOC. */
 lasgd_status lasgd_set_tuning(lasgd_ctx *ctx, const lasgd_tuning *t);
 

@@ -51,8 +51,12 @@ struct lasgd_ctx {
     // device memory (one allocation, carved up)
     char *arena = nullptr;
     float *v = nullptr, *s = nullptr, *z = nullptr, *x32 = nullptr;
-    Tile *tiles = nullptr;
+    Tile *tiles = nullptr;           // the table for the current tile size (one of tiles_by_vec)
     uint32_t ntiles = 0;
+    // one table per tile size ever used (vec = 1, 2, 4), kept until destroy: a graph captured
+    // under one tile size still points at its table after the tile size has been changed
+    Tile *tiles_by_vec[3] = {nullptr, nullptr, nullptr};
+    uint32_t ntiles_by_vec[3] = {0, 0, 0};
     void **xptr = nullptr, **gptr = nullptr;     // device tables [K*n_tensors]
     std::vector<void *> h_xptr, h_gptr;
     std::vector<char> bound;
@@ -126,19 +130,23 @@ std::vector<Tile> build_tiles(const lasgd_ctx &c, int vec)
 
 lasgd_status upload_tiles(lasgd_ctx *c, int vec)
 {
-    std::vector<Tile> t = build_tiles(*c, vec);
-    if (t.size() > 0x7fffffffull / kMaxK) return fail(c, LASGD_ERR_UNSUPPORTED, "too many tiles (%zu)", t.size());
-    Tile *d = nullptr;
-    LASGD_HIP(c, hipMalloc(&d, t.size() * sizeof(Tile)));
-    hipError_t e = hipMemcpy(d, t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        (void)hipFree(d);
-        (void)hipGetLastError();
-        return fail(c, LASGD_ERR_HIP, "tile table upload failed: %s", hipGetErrorString(e));
+    const int slot = vec == 1 ? 0 : vec == 2 ? 1 : 2;
+    if (!c->tiles_by_vec[slot]) {
+        std::vector<Tile> t = build_tiles(*c, vec);
+        if (t.size() > 0x7fffffffull / kMaxK) return fail(c, LASGD_ERR_UNSUPPORTED, "too many tiles (%zu)", t.size());
+        Tile *d = nullptr;
+        LASGD_HIP(c, hipMalloc(&d, t.size() * sizeof(Tile)));
+        hipError_t e = hipMemcpy(d, t.data(), t.size() * sizeof(Tile), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(d);
+            (void)hipGetLastError();
+            return fail(c, LASGD_ERR_HIP, "tile table upload failed: %s", hipGetErrorString(e));
+        }
+        c->tiles_by_vec[slot] = d;
+        c->ntiles_by_vec[slot] = (uint32_t)t.size();
     }
-    if (c->tiles) (void)hipFree(c->tiles);
-    c->tiles = d;
-    c->ntiles = (uint32_t)t.size();
+    c->tiles = c->tiles_by_vec[slot];
+    c->ntiles = c->ntiles_by_vec[slot];
     return LASGD_OK;
 }
 
@@ -416,7 +424,8 @@ lasgd_status check_ready_to_step(lasgd_ctx *c, float lr)
 void release(lasgd_ctx *c)
 {
     if (c->arena) (void)hipFree(c->arena);
-    if (c->tiles) (void)hipFree(c->tiles);
+    for (Tile *t : c->tiles_by_vec)
+        if (t) (void)hipFree(t);
     if (c->xptr) (void)hipFree(c->xptr);
     if (c->evA) (void)hipEventDestroy(c->evA);
     if (c->evZ) (void)hipEventDestroy(c->evZ);

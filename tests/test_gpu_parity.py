@@ -311,6 +311,48 @@ def test_graph_replay_equals_eager(m):
         dev.close()
 
 
+def test_graph_survives_a_change_of_tile_size():
+    """A cycle captured with 256-element tiles is replayed after the context has moved on to
+    1024-element tiles (and back): the graph still points at a live tile table."""
+    import torch
+    from oracle import lasgd_oracle as O32
+    from paper_2203_13085_amd.driver import DeviceReplicas
+    w = W.small(K=3, numels=(9000, 5, 1024, 4099), m=2)
+    x0, grads = packed_inputs(w)
+    wd = [w.weight_decay] * len(w.numels)
+    dev = DeviceReplicas(w, weight_decay=wd)
+    o = O32.Oracle(w.K, w.numels, w.momentum, w.nesterov, wd)
+    try:
+        g = grads(1)
+        o.set_model(x0); dev.load_model(x0); dev.load_grads(g)
+        o.local_step(g, w.lr); o.snapshot()
+        dev.ctx.set_tuning(vec=1)
+        dev.ctx.local_step(w.lr); dev.ctx.snapshot()
+        graph = dev.capture_cycle(w.lr, w.m)
+
+        def oracle_cycle():
+            o.average()
+            for _ in range(w.m):
+                o.local_step(g, w.lr)
+            o.merge(True)
+
+        for vec in (4, 2, 1, 4):
+            dev.ctx.set_tuning(vec=vec)
+            with torch.cuda.stream(dev.main):
+                graph.replay()                       # recorded with vec = 1
+            oracle_cycle()
+            dev.ctx.average()                        # and an eager cycle with the current tile size
+            dev.ctx.local_step(w.lr)
+            dev.ctx.step_merge(w.lr, True)
+            oracle_cycle()
+            for k in range(w.K):
+                assert_close(dev.ctx.read_state(B.STATE_X, k), o.x[k], f"x[{k}] at vec {vec}")
+                assert_close(dev.ctx.read_state(B.STATE_S, k), o.s[k], f"s[{k}] at vec {vec}")
+            assert_close(dev.ctx.read_state(B.STATE_Z), o.z, f"z at vec {vec}")
+    finally:
+        dev.close()
+
+
 def _same_special(got, ref, what):
     """Finite values and infinities bit for bit (+0 == -0 aside); NaN where the oracle has NaN
     (payload and sign of a generated NaN are the processor's business)."""
