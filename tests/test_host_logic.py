@@ -172,6 +172,27 @@ def test_product_path_never_touches_the_oracle():
             assert not re.search(r"(import\s+paper_2203_13085_amd|from\s+paper_2203_13085_amd|liblasgd_hip|hip_runtime|#include\s+\"lasgd)", text), f
 
 
+def test_algorithmic_bytes_match_the_per_unit_figures():
+    """The roofline's numerator: 20 B per replica-parameter for a local step (either storage), 28 B + 4 B/K for
+    the fused step + global update, 4 (K + 1) B per parameter for the mean, 28 B + 8 B/K with the mean inside."""
+    import bench
+    for cfg, (step, sm, av) in {0: (83_886_080, 121_634_816, 20_971_520),
+                                2: (4_089_125_120, 5_827_003_296, 920_053_152),
+                                3: (1_121_559_040, 1_584_202_144, 238_331_296),
+                                4: (16_356_500_480, 23_001_328_800, 3_373_528_224)}.items():
+        w = W.config(cfg)
+        a = bench.algorithmic_bytes(w.K, w.N, w.storage == "bf16")
+        assert (a["local_step"], a["step_merge"], a["average"]) == (step, sm, av)
+        assert a["local_step"] == 20 * w.K * w.N
+        assert a["step_merge"] == 28 * w.K * w.N + 4 * w.N
+        assert a["average"] == 4 * (w.K + 1) * w.N
+        assert a["step_merge_average"] == 28 * w.K * w.N + 8 * w.N
+    # one cycle of the default workload (m = 4): 19.01 GB
+    w = W.config(2)
+    a = bench.algorithmic_bytes(w.K, w.N, False)
+    assert round(((w.m - 1) * a["local_step"] + a["step_merge"] + a["average"]) / 1e9, 2) == 19.01
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
