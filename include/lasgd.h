@@ -36,8 +36,9 @@
  *   lasgd_snapshot, lasgd_average.  Loop iteration without global update
  *   (steps 6-8): lasgd_local_step(eta).  With global update (steps 6-9):
  *   lasgd_step_merge(eta, 1) then lasgd_average -- or, unfused,
- *   lasgd_local_step, lasgd_merge(1), lasgd_average.  The clocks t, t^i and
- *   tau_i are the caller's; the library only enforces a legal order.
+ *   lasgd_local_step, lasgd_merge(1), lasgd_average -- or, everything in one
+ *   pass, lasgd_step_merge_average(eta).  The clocks t, t^i and tau_i are the
+ *   caller's; the library only enforces a legal order.
  */
 #ifndef LASGD_H
 #define LASGD_H
@@ -207,7 +208,8 @@ lasgd_status lasgd_step_merge_average(lasgd_ctx *ctx, float lr);
  *
  * In Algorithm 1 every node runs its own loop: it takes between 1 and tau_max
  * local steps per All-Reduce, with a step size indexed by its own clock, and
- * nodes merge "asynchronously from each other" (Sec. 4).  With K nodes batched
+ * each node takes its global update whenever it notices the result, independently
+ * of the others (Sec. 4).  With K nodes batched
  * on one GPU this becomes a bit mask per call (bit k = replica k takes part)
  * and a step size per replica.  The same masks express the partial All-Reduce
  * the paper proposes as future work (Sec. 6): the mean is taken over the
