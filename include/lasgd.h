@@ -149,7 +149,8 @@ lasgd_status lasgd_init_master(lasgd_ctx *ctx);
 lasgd_status lasgd_local_step(lasgd_ctx *ctx, float lr);
 
 /*
- * "Send x^i to All-Reduce" (Algorithm 1 steps 4 and 9c): s[k] <- x[k].  Main stream.
+ * The send of Algorithm 1 (steps 4 and 9c): the model handed to the All-Reduce is
+ * kept, s[k] <- x[k].  Main stream.
  * Errors: STATE (an average is in flight and not yet merged: the side stream
  * may still be reading s), HIP.
  */
@@ -165,8 +166,8 @@ lasgd_status lasgd_snapshot(lasgd_ctx *ctx);
 lasgd_status lasgd_average(lasgd_ctx *ctx);
 
 /*
- * "All Reduce done?" (Algorithm 1 step 9): *done = 1 if the last average has
- * finished on the device, else 0.  Never blocks.
+ * The test of Algorithm 1 step 9 (has the All-Reduce ended?): *done = 1 if the
+ * last average has finished on the device, else 0.  Never blocks.
  * Errors: INVALID (NULL), STATE (no average launched; or the last average was
  * issued while its stream was being captured into a graph -- a recorded mean
  * runs whenever the graph is replayed and cannot be polled through this call), HIP.
